@@ -1,0 +1,191 @@
+/*
+ * libfq -- mixed-bit weight-only quantized linear layers and token NLL for
+ * AMD MI355X (gfx950).
+ *
+ * The method served here is FlexQuant's hybrid model (arXiv 2501.07139): every
+ * module takes its weights from one of several stored quantized models, so the
+ * bit-width is a per-matrix choice made by a configuration vector (Section
+ * "EQM Generation Philosophy"); arithmetic is FP16 whatever the weight
+ * bit-width (Section "Large Language Model Quantization"); a candidate is
+ * scored by perplexity over calibration token sequences (Algorithm 1,
+ * calibrationEval) and served one token at a time (Section "Introduction").
+ *
+ * Conventions
+ *   - Every function returns FQ_OK (0) or a negative FQ_ERR_* code, never
+ *     throws and never allocates device memory.  fq_last_error() gives a
+ *     thread-local message for the last failure on the calling thread.
+ *   - "host" pointers are ordinary memory; "device" pointers are HIP device
+ *     memory of the current device, 16-byte aligned, owned by the caller and
+ *     only accessed by stream-ordered work queued by the call.
+ *   - `stream` is a hipStream_t passed as void*; NULL means the default
+ *     stream.  Device functions only enqueue work; they do not synchronise.
+ *   - bits is one of 2, 3, 4, 8; group must be 128; K must be a multiple of
+ *     128.  fp16 values cross the boundary as IEEE binary16 bit patterns.
+ *
+ * Packed weight format (device and host, little-endian)
+ *   Rows are padded to Np = 64*ceil(N/64); pad rows hold code 0, scale 0.
+ *   A supertile covers R rows by one group of 128 k, R = 32/64/16/16 for
+ *   bits = 2/3/4/8, and takes R*16*bits bytes (1, 3, 1, 2 planes of 1024
+ *   bytes).  Supertile (n/R, k/128) starts at byte
+ *   ((n/R)*(K/128) + k/128) * R*16*bits.  Inside it, lane l = 16*c + r owns
+ *   the dwords D[j] at byte (j/4)*1024 + 16*l + 4*(j%4): one 128-bit load per
+ *   lane per plane, 1024 contiguous bytes per wavefront.
+ *   With n % R = 16*u + r and k % 128 = 32*s + 8*c + e (t = 8*s + e), the
+ *   weight's chunk is C[i] = D[bits*u + i], i < bits, and its code sits at
+ *     bits 4:  C[s],         bit offset 16*(e%2) + 4*(e/2)
+ *     bits 8:  C[2*s + e/4], bit offset 16*(e%2) + 8*((e%4)/2)
+ *     bits 2:  C[s/2],       bit offset 16*(e%2) + 2*(4*(s%2) + e/2)
+ *     bits 3:  t < 30: C[t/10], bit offset 16*(t%2) + 3*((t%10)/2);
+ *              t = 30: code bit i is bit 15 of C[i]; t = 31: bit 31 of C[i].
+ *   (r, c, s, e) are the row, lane slice, k-step and element of a 16x16x32
+ *   matrix-core operand, so a lane's chunk unpacks straight into operands.
+ *   Scales and zeros are fp16 arrays of Np*(K/128) entries in tile order:
+ *   entry (n, g) is element (n/16)*(K/128)*16 + g*16 + n%16.
+ *   The reconstruction is  w = scale * (code - zero): zeros are in code units.
+ */
+#ifndef FQ_H
+#define FQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define FQ_OK 0
+#define FQ_ERR_NULL (-1)      /* a required pointer is NULL */
+#define FQ_ERR_SHAPE (-2)     /* a size is non-positive or K is not a multiple of 128 */
+#define FQ_ERR_BITS (-3)      /* bits not in {2,3,4,8} */
+#define FQ_ERR_GROUP (-4)     /* group != 128 */
+#define FQ_ERR_ALIGN (-5)     /* a device pointer is not 16-byte aligned */
+#define FQ_ERR_WORKSPACE (-6) /* workspace too small */
+#define FQ_ERR_HIP (-7)       /* a HIP call or kernel launch failed */
+
+/* Message for the last error returned on this thread ("" if none).  Host. */
+const char *fq_last_error(void);
+
+/* Library version string.  Host. */
+const char *fq_version(void);
+
+/* ------------------------------------------------------------------ host --- */
+
+/*
+ * Group-wise round-to-nearest asymmetric min-max quantization (the quantizer is
+ * delegated by the paper, Section "Large Language Model Quantization"; this is
+ * the plain one).  Per row and group of 128 consecutive k, in fp32:
+ *   lo = min(0, min w), hi = max(0, max w);
+ *   hi == lo: scale 1, zero 0, codes 0; otherwise
+ *   scale = fp16((hi - lo) / (2^bits - 1)), raised to the smallest normal fp16
+ *   if zero or subnormal; zero = clamp(rne(-lo / scale), 0, 2^bits - 1);
+ *   code = clamp(rne(w / scale) + zero, 0, 2^bits - 1); rne = half-to-even.
+ * W fp32 [N,K] row-major (host, read).  codes u8 [N,K], scales and zeros fp16
+ * [N, K/128] row-major (host, written).  Multi-threaded over rows.
+ */
+int fq_quantize_rtn(const float *W, int N, int K, int bits, int group,
+                    uint8_t *codes, uint16_t *scales, uint16_t *zeros);
+
+/* Bytes of the packed buffer for an [N,K] matrix: 64*ceil(N/64) * K * bits / 8. 0 on bad arguments. */
+size_t fq_packed_bytes(int N, int K, int bits);
+
+/* Entries of each tiled scale/zero array: 64*ceil(N/64) * K/128.  0 on bad arguments. */
+size_t fq_meta_count(int N, int K, int group);
+
+/*
+ * Pack codes and lay scales/zeros out in the device format described above.
+ * codes u8 [N,K] (values < 2^bits, else FQ_ERR_BITS), scales/zeros fp16
+ * [N,K/128] row-major: host, read.  packed_out (fq_packed_bytes bytes),
+ * scales_out and zeros_out (fq_meta_count entries each): host, written, pad
+ * included.  The caller copies the three outputs to the device unchanged.
+ */
+int fq_pack_groups(const uint8_t *codes, const uint16_t *scales, const uint16_t *zeros,
+                   int N, int K, int bits, int group,
+                   void *packed_out, uint16_t *scales_out, uint16_t *zeros_out);
+
+/* ---------------------------------------------------------------- device --- */
+
+/*
+ * Dequantize a packed matrix to a dense row-major [N,K] array: fp32
+ * (out_is_fp16 == 0): float(scale) * (float(code) - float(zero)), each step
+ * rounded to fp32; or fp16: that value rounded once.  For parity checks.
+ * packed, scales, zeros: device, read.  out: device, written.
+ */
+int fq_dequant(const void *packed, const void *scales, const void *zeros,
+               int N, int K, int bits, int group, void *out, int out_is_fp16, void *stream);
+
+/*
+ * The quantized linear layer of a hybrid model:
+ *   out[m,n] = sum_k x[m,k] * scale[n,k/128] * (code[n,k] - zero[n,k/128]),
+ * fp16 inputs, fp32 accumulation, fp16 output (one rounding).  x fp16 [M,K]
+ * row-major and the packed triple: device, read.  out fp16 [M,N] row-major:
+ * device, written.  M <= 16 runs the bandwidth-bound streaming kernel (decode),
+ * larger M the matrix-core tile kernel (calibration forward).  Any M >= 1,
+ * N >= 1.  Scales and zeros may be any finite fp16 (e.g. zero/2^d after
+ * truncating d code bits, Section "Elastic Serving").
+ */
+int fq_qlinear(const void *x, int M, const void *packed, const void *scales, const void *zeros,
+               int N, int K, int bits, int group, void *out, void *stream);
+
+/* One matrix in all stored bit-widths; index 0..3 = bits 2, 3, 4, 8.  Unused widths may be NULL. */
+typedef struct {
+    const void *packed[4];
+    const void *scales[4];
+    const void *zeros[4];
+    int N, K;
+} fq_matrix;
+
+/* The seven linears of a decoder block: q, k, v, o, gate, up, down. */
+typedef struct {
+    fq_matrix m[7];
+} fq_layer;
+
+/* Workspace bytes fq_stack_forward needs for M rows of a (hidden, ffn) stack. */
+size_t fq_stack_workspace_bytes(int M, int hidden, int ffn);
+
+/*
+ * Forward M rows through L blocks whose matrix j of block l uses the packing
+ * of bit-width bitvec[7*l + j] -- the configuration vector of a hybrid model
+ * (Section "EQM Generation Philosophy").  Synthetic block, every named tensor
+ * fp16, rms(t) = t / sqrt(mean(t^2) + 1e-5) per row:
+ *   u = rms(x); q,k,v = Lq(u), Lk(u), Lv(u); a = rms(q+k+v); o = Lo(a);
+ *   x1 = x + o; u2 = rms(x1); g,p = Lgate(u2), Lup(u2); m = rms(silu(g)*p);
+ *   d = Ldown(m); x_next = rms(x1 + d).
+ * layers: host array of L entries holding device pointers (read during the
+ * call only).  bitvec: host, 7*L entries.  x_in fp16 [M,hidden]: device, read.
+ * x_out fp16 [M,hidden]: device, written (may equal x_in).  workspace: device.
+ * A NULL packing for a selected bit-width fails with FQ_ERR_NULL before any
+ * launch.
+ */
+int fq_stack_forward(const fq_layer *layers, int L, const uint8_t *bitvec,
+                     const void *x_in, int M, void *x_out,
+                     void *workspace, size_t workspace_bytes, void *stream);
+
+/* Single glue steps of the block above, exposed for layer-by-layer parity checks.
+ * All tensors fp16 [M,H] row-major on the device; b and c may be NULL where unused.
+ *   op 0: out = rms(a)              op 1: out = rms(a + b + c)
+ *   op 2: out = a + b               op 3: out = rms(silu(a) * b)
+ *   op 4: out = rms(a + b)
+ */
+int fq_glue(int op, const void *a, const void *b, const void *c, int M, int H, void *out, void *stream);
+
+/*
+ * Unquantized fp16 linear (the vocabulary head): out[m,n] = sum_k x[m,k] W[n,k],
+ * fp32 accumulation, fp16 output.  x [M,K], W [N,K], out [M,N] row-major,
+ * device.  K must be a multiple of 128.
+ */
+int fq_dense_f16(const void *x, int M, const void *W, int N, int K, void *out, void *stream);
+
+/*
+ * Fused log-softmax cross-entropy per token (the quantity whose mean,
+ * exponentiated, is the perplexity calibrationEval returns in Algorithm 1):
+ *   nll[m] = log(sum_v exp(l[m,v] - max_v l[m,v])) + max_v l[m,v] - l[m,label[m]].
+ * logits fp16 [M,V] row-major, labels int32 [M]: device, read.  nll fp32 [M]:
+ * device, written.  A label outside [0,V) marks an ignored position (nll 0).
+ * One pass over the logits.
+ */
+int fq_token_nll(const void *logits, const int32_t *labels, int M, int V, float *nll_out, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FQ_H */

@@ -1,0 +1,282 @@
+"""Python binding of libfq (argument marshalling only).
+
+Every function has the name and meaning of the C entry point declared in
+``include/fq.h``; all arithmetic happens inside the library's HIP kernels (or,
+for the one-off quantize/pack preparation, its host code).  PyTorch is used for
+device memory and streams, numpy for host buffers.  There is no fallback: if the
+built library is missing the import fails.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libfq.so")
+
+BIT_WIDTHS = (2, 3, 4, 8)
+GROUP = 128
+
+FQ_OK = 0
+ERROR_NAMES = {-1: "FQ_ERR_NULL", -2: "FQ_ERR_SHAPE", -3: "FQ_ERR_BITS", -4: "FQ_ERR_GROUP",
+               -5: "FQ_ERR_ALIGN", -6: "FQ_ERR_WORKSPACE", -7: "FQ_ERR_HIP"}
+
+
+class FqError(RuntimeError):
+    def __init__(self, code: int, message: str):
+        super().__init__(f"{ERROR_NAMES.get(code, code)}: {message}")
+        self.code = code
+
+
+class fq_matrix(ctypes.Structure):
+    _fields_ = [("packed", ctypes.c_void_p * 4), ("scales", ctypes.c_void_p * 4), ("zeros", ctypes.c_void_p * 4),
+                ("N", ctypes.c_int), ("K", ctypes.c_int)]
+
+
+class fq_layer(ctypes.Structure):
+    _fields_ = [("m", fq_matrix * 7)]
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is not built; run `python -m paper_2501_07139_amd.build`")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, ci, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+    sig = {
+        "fq_last_error": (ctypes.c_char_p, []),
+        "fq_version": (ctypes.c_char_p, []),
+        "fq_quantize_rtn": (ci, [vp, ci, ci, ci, ci, vp, vp, vp]),
+        "fq_packed_bytes": (sz, [ci, ci, ci]),
+        "fq_meta_count": (sz, [ci, ci, ci]),
+        "fq_pack_groups": (ci, [vp, vp, vp, ci, ci, ci, ci, vp, vp, vp]),
+        "fq_dequant": (ci, [vp, vp, vp, ci, ci, ci, ci, vp, ci, vp]),
+        "fq_qlinear": (ci, [vp, ci, vp, vp, vp, ci, ci, ci, ci, vp, vp]),
+        "fq_stack_workspace_bytes": (sz, [ci, ci, ci]),
+        "fq_stack_forward": (ci, [ctypes.POINTER(fq_layer), ci, vp, vp, ci, vp, vp, sz, vp]),
+        "fq_glue": (ci, [ci, vp, vp, vp, ci, ci, vp, vp]),
+        "fq_dense_f16": (ci, [vp, ci, vp, ci, ci, vp, vp]),
+        "fq_token_nll": (ci, [vp, vp, ci, ci, vp, vp]),
+    }
+    for name, (res, args) in sig.items():
+        fn = getattr(lib, name)
+        fn.restype = res
+        fn.argtypes = args
+    return lib
+
+
+_lib = _load()
+EXPORTS = ("fq_last_error", "fq_version", "fq_quantize_rtn", "fq_packed_bytes", "fq_meta_count", "fq_pack_groups",
+           "fq_dequant", "fq_qlinear", "fq_stack_workspace_bytes", "fq_stack_forward", "fq_glue", "fq_dense_f16",
+           "fq_token_nll")
+
+
+def _check(rc: int) -> None:
+    if rc != FQ_OK:
+        raise FqError(rc, _lib.fq_last_error().decode())
+
+
+def fq_last_error() -> str:
+    return _lib.fq_last_error().decode()
+
+
+def fq_version() -> str:
+    return _lib.fq_version().decode()
+
+
+# ------------------------------------------------------------------ host side
+def _np(a, dtype) -> np.ndarray:
+    a = np.ascontiguousarray(a)
+    if a.dtype != dtype:
+        raise TypeError(f"expected {np.dtype(dtype)}, got {a.dtype}")
+    return a
+
+
+def _hp(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def fq_quantize_rtn(W, bits: int, group: int = GROUP):
+    """fp32 [N,K] -> (codes u8 [N,K], scales fp16 [N,K/128], zeros fp16 [N,K/128]), all host."""
+    W = _np(W, np.float32)
+    N, K = W.shape
+    G = max(K // 128, 1)
+    codes = np.empty((N, K), dtype=np.uint8)
+    scales = np.empty((N, G), dtype=np.float16)
+    zeros = np.empty((N, G), dtype=np.float16)
+    _check(_lib.fq_quantize_rtn(_hp(W), N, K, bits, group, _hp(codes), _hp(scales), _hp(zeros)))
+    return codes, scales, zeros
+
+
+def fq_packed_bytes(N: int, K: int, bits: int) -> int:
+    return _lib.fq_packed_bytes(N, K, bits)
+
+
+def fq_meta_count(N: int, K: int, group: int = GROUP) -> int:
+    return _lib.fq_meta_count(N, K, group)
+
+
+def fq_pack_groups(codes, scales, zeros, bits: int, group: int = GROUP):
+    """Host codes/scales/zeros -> (packed u8, tiled scales fp16, tiled zeros fp16) in the device format."""
+    codes = _np(codes, np.uint8)
+    N, K = codes.shape
+    scales = _np(np.asarray(scales).view(np.float16), np.float16)
+    zeros = _np(np.asarray(zeros).view(np.float16), np.float16)
+    nbytes, nmeta = fq_packed_bytes(N, K, bits), fq_meta_count(N, K, group)
+    packed = np.empty(max(nbytes, 1), dtype=np.uint8)
+    st = np.empty(max(nmeta, 1), dtype=np.float16)
+    zt = np.empty(max(nmeta, 1), dtype=np.float16)
+    _check(_lib.fq_pack_groups(_hp(codes), _hp(scales), _hp(zeros), N, K, bits, group, _hp(packed), _hp(st), _hp(zt)))
+    return packed, st, zt
+
+
+# ---------------------------------------------------------------- device side
+def _torch():
+    import torch
+
+    return torch
+
+
+def _dp(t) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        return _torch().cuda.current_stream().cuda_stream or None
+    if isinstance(stream, int):
+        return stream or None
+    return stream.cuda_stream or None
+
+
+def _dev(t, dtype, what: str):
+    torch = _torch()
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError(f"{what} must be a device tensor")
+    if t.dtype != dtype or not t.is_contiguous():
+        raise TypeError(f"{what} must be contiguous {dtype}, got {t.dtype}")
+    return t
+
+
+class PackedMatrix:
+    """Device copies of one matrix in one bit-width (packed codes, tiled scales, tiled zeros)."""
+
+    def __init__(self, packed, scales, zeros, N: int, K: int, bits: int):
+        self.packed, self.scales, self.zeros = packed, scales, zeros
+        self.N, self.K, self.bits = N, K, bits
+
+    @classmethod
+    def from_host(cls, codes, scales, zeros, bits: int, device="cuda"):
+        torch = _torch()
+        N, K = codes.shape
+        p, s, z = fq_pack_groups(codes, scales, zeros, bits)
+        return cls(torch.from_numpy(p).to(device), torch.from_numpy(s.view(np.int16)).to(device).view(torch.float16),
+                   torch.from_numpy(z.view(np.int16)).to(device).view(torch.float16), N, K, bits)
+
+    @property
+    def nbytes(self) -> int:
+        """Algorithmic bytes of this matrix: packed codes + fp16 scales + fp16 zeros."""
+        return self.N * self.K * self.bits // 8 + 2 * 2 * self.N * (self.K // 128)
+
+
+def fq_dequant(w: PackedMatrix, fp16: bool = False, stream=None):
+    torch = _torch()
+    out = torch.empty((w.N, w.K), dtype=torch.float16 if fp16 else torch.float32, device=w.packed.device)
+    _check(_lib.fq_dequant(_dp(w.packed), _dp(w.scales), _dp(w.zeros), w.N, w.K, w.bits, GROUP, _dp(out), int(fp16),
+                           _stream(stream)))
+    return out
+
+
+def fq_qlinear(x, w: PackedMatrix, out=None, stream=None, group: int = GROUP):
+    torch = _torch()
+    x = _dev(x, torch.float16, "x")
+    M, K = x.shape
+    if K != w.K:
+        raise FqError(-2, f"x has K={K}, weights have K={w.K}")
+    if out is None:
+        out = torch.empty((M, w.N), dtype=torch.float16, device=x.device)
+    _dev(out, torch.float16, "out")
+    _check(_lib.fq_qlinear(_dp(x), M, _dp(w.packed), _dp(w.scales), _dp(w.zeros), w.N, w.K, w.bits, group, _dp(out),
+                           _stream(stream)))
+    return out
+
+
+class Stack:
+    """Host table of device pointers for L blocks x 7 matrices x the stored bit-widths."""
+
+    def __init__(self, layers: Sequence[Sequence[dict]]):
+        # layers[l][j] maps bits -> PackedMatrix
+        self.layers = layers
+        self.L = len(layers)
+        self.table = (fq_layer * self.L)()
+        for l, mats in enumerate(layers):
+            if len(mats) != 7:
+                raise ValueError("a block has seven matrices")
+            for j, by_bits in enumerate(mats):
+                any_w = next(iter(by_bits.values()))
+                entry = self.table[l].m[j]
+                entry.N, entry.K = any_w.N, any_w.K
+                for i, b in enumerate(BIT_WIDTHS):
+                    w = by_bits.get(b)
+                    entry.packed[i] = _dp(w.packed) if w else None
+                    entry.scales[i] = _dp(w.scales) if w else None
+                    entry.zeros[i] = _dp(w.zeros) if w else None
+        self.hidden = layers[0][0][next(iter(layers[0][0]))].K
+        self.ffn = layers[0][4][next(iter(layers[0][4]))].N
+
+
+def fq_stack_workspace_bytes(M: int, hidden: int, ffn: int) -> int:
+    return _lib.fq_stack_workspace_bytes(M, hidden, ffn)
+
+
+def fq_stack_forward(stack: Stack, bitvec, x, out=None, workspace=None, stream=None):
+    torch = _torch()
+    x = _dev(x, torch.float16, "x")
+    M = x.shape[0]
+    bitvec = _np(np.asarray(bitvec, dtype=np.uint8), np.uint8)
+    if bitvec.size != 7 * stack.L:
+        raise FqError(-2, f"bitvec has {bitvec.size} entries, stack needs {7 * stack.L}")
+    if out is None:
+        out = torch.empty_like(x)
+    if workspace is None:
+        workspace = torch.empty(fq_stack_workspace_bytes(M, stack.hidden, stack.ffn), dtype=torch.uint8, device=x.device)
+    _check(_lib.fq_stack_forward(stack.table, stack.L, _hp(bitvec), _dp(x), M, _dp(out), _dp(workspace),
+                                 workspace.numel(), _stream(stream)))
+    return out
+
+
+def fq_glue(op: int, a, b=None, c=None, out=None, stream=None):
+    torch = _torch()
+    a = _dev(a, torch.float16, "a")
+    M, H = a.shape
+    if out is None:
+        out = torch.empty_like(a)
+    _check(_lib.fq_glue(op, _dp(a), _dp(b), _dp(c), M, H, _dp(out), _stream(stream)))
+    return out
+
+
+def fq_dense_f16(x, W, out=None, stream=None):
+    torch = _torch()
+    x = _dev(x, torch.float16, "x")
+    W = _dev(W, torch.float16, "W")
+    M, K = x.shape
+    N = W.shape[0]
+    if W.shape[1] != K:
+        raise FqError(-2, f"x has K={K}, W has K={W.shape[1]}")
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float16, device=x.device)
+    _check(_lib.fq_dense_f16(_dp(x), M, _dp(W), N, K, _dp(out), _stream(stream)))
+    return out
+
+
+def fq_token_nll(logits, labels, out=None, stream=None):
+    torch = _torch()
+    logits = _dev(logits, torch.float16, "logits")
+    labels = _dev(labels, torch.int32, "labels")
+    M, V = logits.shape
+    if out is None:
+        out = torch.empty(M, dtype=torch.float32, device=logits.device)
+    _check(_lib.fq_token_nll(_dp(logits), _dp(labels), M, V, _dp(out), _stream(stream)))
+    return out

@@ -1,0 +1,191 @@
+// C-ABI entry points of the device half: argument checks, dispatch, and the
+// block/stack driver that applies a hybrid model's configuration vector
+// (FlexQuant, arXiv 2501.07139, Section "EQM Generation Philosophy": each
+// module takes its parameters from one stored quantized model).
+#include "fq.h"
+#include "fq_internal.h"
+
+#include <hip/hip_runtime.h>
+
+namespace {
+
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int check_hip(int e, const char *what)
+{
+    if (e == 0)
+        return FQ_OK;
+    return fq_fail(FQ_ERR_HIP, "%s: %s", what, hipGetErrorString((hipError_t)e));
+}
+
+int check_matrix(const char *fn, const void *packed, const void *scales, const void *zeros, int N, int K,
+                 int bits, int group)
+{
+    if (!packed || !scales || !zeros)
+        return fq_fail(FQ_ERR_NULL, "%s: NULL weight pointer", fn);
+    if (fq_bits_index(bits) < 0)
+        return fq_fail(FQ_ERR_BITS, "%s: bits=%d not in {2,3,4,8}", fn, bits);
+    if (group != 128)
+        return fq_fail(FQ_ERR_GROUP, "%s: group=%d, only 128 is supported", fn, group);
+    if (N <= 0 || K <= 0 || K % 128 != 0)
+        return fq_fail(FQ_ERR_SHAPE, "%s: N=%d K=%d (K must be a positive multiple of 128)", fn, N, K);
+    if (!aligned16(packed) || !aligned16(scales) || !aligned16(zeros))
+        return fq_fail(FQ_ERR_ALIGN, "%s: weight pointers must be 16-byte aligned", fn);
+    return FQ_OK;
+}
+
+int qlinear_checked(const void *x, int M, const fq_packed_ref &w, void *out, fq_stream st)
+{
+    int e = (M <= 16) ? fq_launch_gemv(x, M, w, out, st) : fq_launch_gemm(x, M, w, out, st);
+    return check_hip(e, "fq_qlinear launch");
+}
+
+constexpr int kMaxGlueH = 16384;
+
+size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
+
+} // namespace
+
+extern "C" int fq_dequant(const void *packed, const void *scales, const void *zeros, int N, int K, int bits,
+                          int group, void *out, int out_is_fp16, void *stream)
+{
+    if (int rc = check_matrix("fq_dequant", packed, scales, zeros, N, K, bits, group))
+        return rc;
+    if (!out)
+        return fq_fail(FQ_ERR_NULL, "fq_dequant: NULL output");
+    fq_packed_ref w{packed, scales, zeros, N, K, bits};
+    return check_hip(fq_launch_dequant(w, out, out_is_fp16, static_cast<fq_stream>(stream)), "fq_dequant launch");
+}
+
+extern "C" int fq_qlinear(const void *x, int M, const void *packed, const void *scales, const void *zeros,
+                          int N, int K, int bits, int group, void *out, void *stream)
+{
+    if (int rc = check_matrix("fq_qlinear", packed, scales, zeros, N, K, bits, group))
+        return rc;
+    if (!x || !out)
+        return fq_fail(FQ_ERR_NULL, "fq_qlinear: NULL activation or output pointer");
+    if (M <= 0)
+        return fq_fail(FQ_ERR_SHAPE, "fq_qlinear: M=%d", M);
+    if (!aligned16(x) || !aligned16(out))
+        return fq_fail(FQ_ERR_ALIGN, "fq_qlinear: x and out must be 16-byte aligned");
+    fq_packed_ref w{packed, scales, zeros, N, K, bits};
+    return qlinear_checked(x, M, w, out, static_cast<fq_stream>(stream));
+}
+
+extern "C" int fq_dense_f16(const void *x, int M, const void *W, int N, int K, void *out, void *stream)
+{
+    if (!x || !W || !out)
+        return fq_fail(FQ_ERR_NULL, "fq_dense_f16: NULL argument");
+    if (M <= 0 || N <= 0 || K <= 0 || K % 128 != 0)
+        return fq_fail(FQ_ERR_SHAPE, "fq_dense_f16: M=%d N=%d K=%d (K must be a positive multiple of 128)", M, N, K);
+    if (!aligned16(x) || !aligned16(W) || !aligned16(out))
+        return fq_fail(FQ_ERR_ALIGN, "fq_dense_f16: pointers must be 16-byte aligned");
+    return check_hip(fq_launch_dense(x, M, W, N, K, out, static_cast<fq_stream>(stream)), "fq_dense_f16 launch");
+}
+
+extern "C" int fq_glue(int op, const void *a, const void *b, const void *c, int M, int H, void *out, void *stream)
+{
+    if (op < 0 || op > 4)
+        return fq_fail(FQ_ERR_SHAPE, "fq_glue: op=%d not in 0..4", op);
+    if (!a || !out || (op != 0 && !b) || (op == 1 && !c))
+        return fq_fail(FQ_ERR_NULL, "fq_glue: NULL argument for op %d", op);
+    if (M <= 0 || H <= 0 || H % 8 != 0 || H > kMaxGlueH)
+        return fq_fail(FQ_ERR_SHAPE, "fq_glue: M=%d H=%d (H must be a multiple of 8, at most %d)", M, H, kMaxGlueH);
+    if (!aligned16(a) || !aligned16(out) || (b && !aligned16(b)) || (c && !aligned16(c)))
+        return fq_fail(FQ_ERR_ALIGN, "fq_glue: pointers must be 16-byte aligned");
+    return check_hip(fq_launch_glue(op, a, b, c, M, H, out, static_cast<fq_stream>(stream)), "fq_glue launch");
+}
+
+extern "C" int fq_token_nll(const void *logits, const int32_t *labels, int M, int V, float *nll_out, void *stream)
+{
+    if (!logits || !labels || !nll_out)
+        return fq_fail(FQ_ERR_NULL, "fq_token_nll: NULL argument");
+    if (M <= 0 || V <= 0)
+        return fq_fail(FQ_ERR_SHAPE, "fq_token_nll: M=%d V=%d", M, V);
+    if (!aligned16(logits))
+        return fq_fail(FQ_ERR_ALIGN, "fq_token_nll: logits must be 16-byte aligned");
+    return check_hip(fq_launch_nll(logits, labels, M, V, nll_out, static_cast<fq_stream>(stream)), "fq_token_nll launch");
+}
+
+// Workspace: u, q, k, v, a, o, x1, u2, d, xcur (hidden wide) and g, p, m (ffn wide).
+extern "C" size_t fq_stack_workspace_bytes(int M, int hidden, int ffn)
+{
+    if (M <= 0 || hidden <= 0 || ffn <= 0)
+        return 0;
+    const size_t h = align_up((size_t)M * hidden * 2), f = align_up((size_t)M * ffn * 2);
+    return 10 * h + 3 * f;
+}
+
+extern "C" int fq_stack_forward(const fq_layer *layers, int L, const uint8_t *bitvec, const void *x_in, int M,
+                                void *x_out, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!layers || !bitvec || !x_in || !x_out || !workspace)
+        return fq_fail(FQ_ERR_NULL, "fq_stack_forward: NULL argument");
+    if (L <= 0 || M <= 0)
+        return fq_fail(FQ_ERR_SHAPE, "fq_stack_forward: L=%d M=%d", L, M);
+    const int H = layers[0].m[0].K, F = layers[0].m[4].N;
+    if (H <= 0 || F <= 0 || H % 128 != 0 || F % 128 != 0 || H > kMaxGlueH || F > kMaxGlueH)
+        return fq_fail(FQ_ERR_SHAPE, "fq_stack_forward: hidden=%d ffn=%d must be multiples of 128, at most %d", H, F,
+                       kMaxGlueH);
+    // validate every selected packing before anything is launched
+    fq_packed_ref sel[7];
+    for (int l = 0; l < L; ++l)
+        for (int j = 0; j < 7; ++j) {
+            const fq_matrix &mx = layers[l].m[j];
+            const int wantN = (j == 4 || j == 5) ? F : H, wantK = (j == 6) ? F : H;
+            if (mx.N != wantN || mx.K != wantK)
+                return fq_fail(FQ_ERR_SHAPE, "fq_stack_forward: layer %d matrix %d is %dx%d, expected %dx%d", l, j,
+                               mx.N, mx.K, wantN, wantK);
+            const int bi = fq_bits_index(bitvec[7 * l + j]);
+            if (bi < 0)
+                return fq_fail(FQ_ERR_BITS, "fq_stack_forward: bitvec[%d]=%d not in {2,3,4,8}", 7 * l + j,
+                               (int)bitvec[7 * l + j]);
+            if (!mx.packed[bi] || !mx.scales[bi] || !mx.zeros[bi])
+                return fq_fail(FQ_ERR_NULL, "fq_stack_forward: layer %d matrix %d has no %d-bit packing", l, j,
+                               (int)bitvec[7 * l + j]);
+            if (!aligned16(mx.packed[bi]) || !aligned16(mx.scales[bi]) || !aligned16(mx.zeros[bi]))
+                return fq_fail(FQ_ERR_ALIGN, "fq_stack_forward: layer %d matrix %d is not 16-byte aligned", l, j);
+        }
+    if (workspace_bytes < fq_stack_workspace_bytes(M, H, F))
+        return fq_fail(FQ_ERR_WORKSPACE, "fq_stack_forward: workspace of %zu bytes, need %zu", workspace_bytes,
+                       fq_stack_workspace_bytes(M, H, F));
+    if (!aligned16(x_in) || !aligned16(x_out) || !aligned16(workspace))
+        return fq_fail(FQ_ERR_ALIGN, "fq_stack_forward: x_in, x_out and workspace must be 16-byte aligned");
+
+    fq_stream st = static_cast<fq_stream>(stream);
+    const size_t hb = align_up((size_t)M * H * 2), fb = align_up((size_t)M * F * 2);
+    char *ws = static_cast<char *>(workspace);
+    void *u = ws, *q = ws + hb, *k = ws + 2 * hb, *v = ws + 3 * hb, *a = ws + 4 * hb, *o = ws + 5 * hb,
+         *x1 = ws + 6 * hb, *u2 = ws + 7 * hb, *d = ws + 8 * hb, *xc = ws + 9 * hb;
+    void *g = ws + 10 * hb, *p = ws + 10 * hb + fb, *mm = ws + 10 * hb + 2 * fb;
+
+    const void *xcur = x_in;
+    for (int l = 0; l < L; ++l) {
+        for (int j = 0; j < 7; ++j) {
+            const fq_matrix &mx = layers[l].m[j];
+            const int bits = bitvec[7 * l + j], bi = fq_bits_index(bits);
+            sel[j] = fq_packed_ref{mx.packed[bi], mx.scales[bi], mx.zeros[bi], mx.N, mx.K, bits};
+        }
+        void *xnext = (l == L - 1) ? x_out : xc;
+        int rc;
+#define FQ_STEP(call) \
+    if ((rc = (call)) != FQ_OK) \
+        return rc
+        FQ_STEP(check_hip(fq_launch_glue(0, xcur, nullptr, nullptr, M, H, u, st), "glue rms"));
+        FQ_STEP(qlinear_checked(u, M, sel[0], q, st));
+        FQ_STEP(qlinear_checked(u, M, sel[1], k, st));
+        FQ_STEP(qlinear_checked(u, M, sel[2], v, st));
+        FQ_STEP(check_hip(fq_launch_glue(1, q, k, v, M, H, a, st), "glue rms(q+k+v)"));
+        FQ_STEP(qlinear_checked(a, M, sel[3], o, st));
+        FQ_STEP(check_hip(fq_launch_glue(2, xcur, o, nullptr, M, H, x1, st), "glue add"));
+        FQ_STEP(check_hip(fq_launch_glue(0, x1, nullptr, nullptr, M, H, u2, st), "glue rms"));
+        FQ_STEP(qlinear_checked(u2, M, sel[4], g, st));
+        FQ_STEP(qlinear_checked(u2, M, sel[5], p, st));
+        FQ_STEP(check_hip(fq_launch_glue(3, g, p, nullptr, M, F, mm, st), "glue rms(silu*mul)"));
+        FQ_STEP(qlinear_checked(mm, M, sel[6], d, st));
+        FQ_STEP(check_hip(fq_launch_glue(4, x1, d, nullptr, M, H, xnext, st), "glue rms(add)"));
+#undef FQ_STEP
+        xcur = xnext;
+    }
+    return FQ_OK;
+}

@@ -1,0 +1,165 @@
+// Device-side helpers: vector types, the packed-format constants and the
+// per-bit-width unpack routines.  One specialisation per bit-width; nothing here
+// branches on the bit-width at run time.
+#ifndef FQ_DEVICE_H
+#define FQ_DEVICE_H
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+typedef _Float16 h4 __attribute__((ext_vector_type(4)));
+typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+typedef float f4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u2v __attribute__((ext_vector_type(2)));
+typedef uint32_t u4v __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ h2 as_h2(uint32_t u) { return __builtin_bit_cast(h2, u); }
+__device__ __forceinline__ uint32_t as_u32(h2 h) { return __builtin_bit_cast(uint32_t, h); }
+
+// Packed-format constants.  A supertile is ROWS rows by 128 k and holds
+// ROWS/16 sixteen-row sub-blocks; each lane owns BITS dwords per sub-block.
+template <int BITS>
+struct Fmt;
+template <>
+struct Fmt<2> { static constexpr int ROWS = 32, SUB = 2, PLANES = 1; };
+template <>
+struct Fmt<3> { static constexpr int ROWS = 64, SUB = 4, PLANES = 3; };
+template <>
+struct Fmt<4> { static constexpr int ROWS = 16, SUB = 1, PLANES = 1; };
+template <>
+struct Fmt<8> { static constexpr int ROWS = 16, SUB = 1, PLANES = 2; };
+
+template <int BITS>
+__host__ __device__ constexpr int tile_dwords() { return Fmt<BITS>::ROWS * 4 * BITS; }
+
+// Dword j of lane `lane` inside a supertile (dword offset from the supertile base).
+__device__ __forceinline__ int lane_dword(int j, int lane) { return (j >> 2) * 256 + lane * 4 + (j & 3); }
+
+// Load the BITS dwords of sub-block `u` owned by `lane`.  Adjacent dwords merge
+// into 64/96/128-bit loads where the format makes them contiguous.
+template <int BITS>
+__device__ __forceinline__ void load_chunk(const uint32_t *tile, int u, int lane, uint32_t (&C)[BITS])
+{
+    if constexpr (BITS == 4) {
+        u4v v = *reinterpret_cast<const u4v *>(tile + lane * 4);
+        C[0] = v.x; C[1] = v.y; C[2] = v.z; C[3] = v.w;
+    } else if constexpr (BITS == 8) {
+        u4v a = *reinterpret_cast<const u4v *>(tile + lane * 4);
+        u4v b = *reinterpret_cast<const u4v *>(tile + 256 + lane * 4);
+        C[0] = a.x; C[1] = a.y; C[2] = a.z; C[3] = a.w;
+        C[4] = b.x; C[5] = b.y; C[6] = b.z; C[7] = b.w;
+    } else if constexpr (BITS == 2) {
+        u2v v = *reinterpret_cast<const u2v *>(tile + lane * 4 + 2 * u);
+        C[0] = v.x; C[1] = v.y;
+    } else {
+#pragma unroll
+        for (int i = 0; i < 3; ++i)
+            C[i] = tile[lane_dword(3 * u + i, lane)];
+    }
+}
+
+// Plain integer code of element t = 8*s + e of a chunk: the format read literally.
+template <int BITS>
+__device__ __forceinline__ uint32_t code_at(const uint32_t (&C)[BITS], int t)
+{
+    const int s = t >> 3, e = t & 7;
+    const int half = 16 * (e & 1);
+    if constexpr (BITS == 4) {
+        return (C[s] >> (half + 4 * (e >> 1))) & 0xfu;
+    } else if constexpr (BITS == 8) {
+        return (C[2 * s + (e >> 2)] >> (half + 8 * ((e & 3) >> 1))) & 0xffu;
+    } else if constexpr (BITS == 2) {
+        return (C[s >> 1] >> (half + 2 * (4 * (s & 1) + (e >> 1)))) & 0x3u;
+    } else {
+        if (t < 30)
+            return (C[t / 10] >> (half + 3 * ((t % 10) >> 1))) & 0x7u;
+        const int b = (t == 30) ? 15 : 31;
+        return ((C[0] >> b) & 1u) | (((C[1] >> b) & 1u) << 1) | (((C[2] >> b) & 1u) << 2);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Fast unpack.  A code field that sits inside the low 10 bits of a 16-bit half
+// becomes an fp16 number by OR-ing in the exponent of 1024: the half then reads
+// 1024 + code * 2^p, p the field's bit position.  One fused multiply-add by
+// (2^-p, -1024 * 2^-p) turns a pair of them into the exact codes.  Fields are
+// laid out so that the two weights of a pair share p and sit 16 bits apart.
+// q[4*s + v] holds elements e = 2v (low half) and 2v+1 (high half) of k-step s.
+// ---------------------------------------------------------------------------
+#define FQ_EXP1024 0x64006400u
+
+template <int P>
+__device__ __forceinline__ h2 debias(uint32_t biased)
+{
+    constexpr float mul = 1.0f / (float)(1 << P);
+    const h2 m = {(_Float16)mul, (_Float16)mul};
+    const h2 a = {(_Float16)(-1024.0f * mul), (_Float16)(-1024.0f * mul)};
+    return __builtin_elementwise_fma(as_h2(biased), m, a);
+}
+
+template <int BITS>
+__device__ __forceinline__ void unpack_codes(const uint32_t (&C)[BITS], h2 (&q)[16])
+{
+    if constexpr (BITS == 4) {
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const uint32_t w = C[s], t = w >> 8;
+            q[4 * s + 0] = debias<0>((w & 0x000f000fu) | FQ_EXP1024);
+            q[4 * s + 1] = debias<4>((w & 0x00f000f0u) | FQ_EXP1024);
+            q[4 * s + 2] = debias<0>((t & 0x000f000fu) | FQ_EXP1024);
+            q[4 * s + 3] = debias<4>((t & 0x00f000f0u) | FQ_EXP1024);
+        }
+    } else if constexpr (BITS == 2) {
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const uint32_t w = C[j], t = w >> 10;
+            q[8 * j + 0] = debias<0>((w & 0x00030003u) | FQ_EXP1024);
+            q[8 * j + 1] = debias<2>((w & 0x000c000cu) | FQ_EXP1024);
+            q[8 * j + 2] = debias<4>((w & 0x00300030u) | FQ_EXP1024);
+            q[8 * j + 3] = debias<6>((w & 0x00c000c0u) | FQ_EXP1024);
+            q[8 * j + 4] = debias<8>((w & 0x03000300u) | FQ_EXP1024);
+            q[8 * j + 5] = debias<0>((t & 0x00030003u) | FQ_EXP1024);
+            q[8 * j + 6] = debias<2>((t & 0x000c000cu) | FQ_EXP1024);
+            q[8 * j + 7] = debias<4>((t & 0x00300030u) | FQ_EXP1024);
+        }
+    } else if constexpr (BITS == 8) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const uint32_t w = C[j];
+            // bytes 0 and 2 form one pair, bytes 1 and 3 the next
+            q[2 * j + 0] = debias<0>((w & 0x00ff00ffu) | FQ_EXP1024);
+            q[2 * j + 1] = debias<0>(((w >> 8) & 0x00ff00ffu) | FQ_EXP1024);
+        }
+    } else {
+#pragma unroll
+        for (int d = 0; d < 3; ++d) {
+            const uint32_t w = C[d], t = w >> 9;
+            q[5 * d + 0] = debias<0>((w & 0x00070007u) | FQ_EXP1024);
+            q[5 * d + 1] = debias<3>((w & 0x00380038u) | FQ_EXP1024);
+            q[5 * d + 2] = debias<6>((w & 0x01c001c0u) | FQ_EXP1024);
+            q[5 * d + 3] = debias<0>((t & 0x00070007u) | FQ_EXP1024);
+            q[5 * d + 4] = debias<3>((t & 0x00380038u) | FQ_EXP1024);
+        }
+        uint32_t sp = ((C[0] >> 15) & 0x00010001u) | FQ_EXP1024;
+        sp |= (C[1] >> 14) & 0x00020002u;
+        sp |= (C[2] >> 13) & 0x00040004u;
+        q[15] = debias<0>(sp);
+    }
+}
+
+// Operand for k-step s of a 16x16x32 matrix-core instruction from four pairs.
+__device__ __forceinline__ h8 make_h8(h2 a, h2 b, h2 c, h2 d)
+{
+    h8 r;
+    r[0] = a[0]; r[1] = a[1]; r[2] = b[0]; r[3] = b[1];
+    r[4] = c[0]; r[5] = c[1]; r[6] = d[0]; r[7] = d[1];
+    return r;
+}
+
+__device__ __forceinline__ f4 mfma16x16x32(h8 a, h8 b, f4 c)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
+}
+
+#endif

@@ -1,0 +1,31 @@
+// Declarations shared by the translation units of libfq (not part of the ABI).
+#ifndef FQ_INTERNAL_H
+#define FQ_INTERNAL_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+int fq_fail(int code, const char *fmt, ...) __attribute__((format(printf, 2, 3)));
+int fq_bits_index(int bits);         // 2,3,4,8 -> 0..3, else -1
+int fq_rows_per_supertile(int bits); // 32,64,16,16
+
+struct ihipStream_t;
+typedef ihipStream_t *fq_stream;
+
+// One packed matrix as the kernels see it.
+struct fq_packed_ref {
+    const void *packed;
+    const void *scales;
+    const void *zeros;
+    int N, K, bits;
+};
+
+// Launchers.  Arguments are validated by the callers in fq_api.hip; each returns a hipError_t as int.
+int fq_launch_dequant(const fq_packed_ref &w, void *out, int out_is_fp16, fq_stream st);
+int fq_launch_gemv(const void *x, int M, const fq_packed_ref &w, void *out, fq_stream st);
+int fq_launch_gemm(const void *x, int M, const fq_packed_ref &w, void *out, fq_stream st);
+int fq_launch_dense(const void *x, int M, const void *W, int N, int K, void *out, fq_stream st);
+int fq_launch_glue(int op, const void *a, const void *b, const void *c, int M, int H, void *out, fq_stream st);
+int fq_launch_nll(const void *logits, const int32_t *labels, int M, int V, float *nll, fq_stream st);
+
+#endif

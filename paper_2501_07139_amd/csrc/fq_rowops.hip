@@ -1,0 +1,231 @@
+// Row-wise kernels: the glue between the linears of the synthetic block, the
+// dense dump of a packed matrix, and the fused log-softmax cross-entropy that
+// turns head logits into the per-token loss behind the perplexity score
+// (FlexQuant, arXiv 2501.07139, Algorithm 1, calibrationEval).  All are
+// bandwidth-bound: one pass over their inputs with 128-bit loads.
+#include "fq_device.h"
+#include "fq_internal.h"
+
+namespace {
+
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1)
+        v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+__device__ __forceinline__ float wave_max(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1)
+        v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+
+// ------------------------------------------------------------------ glue
+// One workgroup of 256 threads per row; the row lives in registers between the
+// sum-of-squares pass and the scaling pass (H <= 256*8*MAXC halves).
+constexpr int GLUE_MAXC = 8;
+
+template <int OP>
+__global__ __launch_bounds__(256) void glue_kernel(const _Float16 *__restrict__ a, const _Float16 *__restrict__ b,
+                                                   const _Float16 *__restrict__ c, int H,
+                                                   _Float16 *__restrict__ out)
+{
+    const size_t row = (size_t)blockIdx.x * H;
+    const int chunks = H >> 3;
+    float t[GLUE_MAXC][8];
+    float ss = 0.f;
+#pragma unroll
+    for (int i = 0; i < GLUE_MAXC; ++i) {
+        const int ch = threadIdx.x + 256 * i;
+        if (ch < chunks) {
+            const h8 va = *reinterpret_cast<const h8 *>(a + row + ch * 8);
+            h8 vb = va, vc = va;
+            if constexpr (OP != 0)
+                vb = *reinterpret_cast<const h8 *>(b + row + ch * 8);
+            if constexpr (OP == 1)
+                vc = *reinterpret_cast<const h8 *>(c + row + ch * 8);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                float v;
+                if constexpr (OP == 0)
+                    v = (float)va[e];
+                else if constexpr (OP == 1)
+                    v = (float)va[e] + (float)vb[e] + (float)vc[e];
+                else if constexpr (OP == 2 || OP == 4)
+                    v = (float)va[e] + (float)vb[e];
+                else {
+                    const float g = (float)va[e];
+                    v = g / (1.0f + __expf(-g)) * (float)vb[e];
+                }
+                t[i][e] = v;
+                ss += v * v;
+            }
+        }
+    }
+    float inv = 1.0f;
+    if constexpr (OP != 2) {
+        __shared__ float part[4];
+        ss = wave_sum(ss);
+        if ((threadIdx.x & 63) == 0)
+            part[threadIdx.x >> 6] = ss;
+        __syncthreads();
+        ss = part[0] + part[1] + part[2] + part[3];
+        inv = 1.0f / sqrtf(ss / (float)H + 1e-5f);
+    }
+#pragma unroll
+    for (int i = 0; i < GLUE_MAXC; ++i) {
+        const int ch = threadIdx.x + 256 * i;
+        if (ch < chunks) {
+            h8 o;
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                o[e] = (_Float16)(t[i][e] * inv);
+            *reinterpret_cast<h8 *>(out + row + ch * 8) = o;
+        }
+    }
+}
+
+// ------------------------------------------------------------------- NLL
+// One workgroup per token row; each thread keeps a running (max, sum of
+// exp(l - max)) over its 16-byte chunks, then the pairs are merged across the
+// wavefront and the workgroup.  The label's logit is read directly.
+__device__ __forceinline__ void lse_merge(float &m, float &s, float m2, float s2)
+{
+    const float mx = fmaxf(m, m2);
+    if (mx == -INFINITY) {
+        m = mx;
+        s = 0.f;
+        return;
+    }
+    s = s * __expf(m - mx) + s2 * __expf(m2 - mx);
+    m = mx;
+}
+
+__global__ __launch_bounds__(256) void nll_kernel(const _Float16 *__restrict__ logits,
+                                                  const int32_t *__restrict__ labels, int V,
+                                                  float *__restrict__ nll)
+{
+    const int row = blockIdx.x;
+    const int label = labels[row];
+    if (label < 0 || label >= V) { // uniform across the workgroup
+        if (threadIdx.x == 0)
+            nll[row] = 0.f;
+        return;
+    }
+    const _Float16 *l = logits + (size_t)row * V;
+    float mx = -INFINITY, se = 0.f;
+    // rows start 16-byte aligned only if V % 8 == 0; otherwise take the scalar route
+    if ((V & 7) == 0) {
+        const int chunks = V >> 3;
+        for (int ch = threadIdx.x; ch < chunks; ch += 256) {
+            const h8 v = *reinterpret_cast<const h8 *>(l + ch * 8);
+            float cm = (float)v[0];
+#pragma unroll
+            for (int e = 1; e < 8; ++e)
+                cm = fmaxf(cm, (float)v[e]);
+            float cs = 0.f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                cs += __expf((float)v[e] - cm);
+            lse_merge(mx, se, cm, cs);
+        }
+    } else {
+        for (int i = threadIdx.x; i < V; i += 256)
+            lse_merge(mx, se, (float)l[i], 1.0f);
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const float m2 = __shfl_xor(mx, o, 64), s2 = __shfl_xor(se, o, 64);
+        lse_merge(mx, se, m2, s2);
+    }
+    __shared__ float pm[4], ps[4];
+    if ((threadIdx.x & 63) == 0) {
+        pm[threadIdx.x >> 6] = mx;
+        ps[threadIdx.x >> 6] = se;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float m = pm[0], s = ps[0];
+        for (int w = 1; w < 4; ++w)
+            lse_merge(m, s, pm[w], ps[w]);
+        nll[row] = logf(s) + m - (float)l[label];
+    }
+}
+
+// --------------------------------------------------------------- dequant
+// Dense dump of a packed matrix, one thread per (sixteen-row block, group, lane)
+// chunk: reads the format literally (integer field extraction), then
+// float(scale) * (float(code) - float(zero)) with both steps rounded to fp32.
+template <int BITS>
+__global__ __launch_bounds__(64) void dequant_kernel(const uint32_t *__restrict__ packed,
+                                                     const _Float16 *__restrict__ scales,
+                                                     const _Float16 *__restrict__ zeros, int N, int K,
+                                                     void *__restrict__ out, int out_is_fp16)
+{
+    constexpr int SUB = Fmt<BITS>::SUB;
+    const int G = K >> 7;
+    const int g = blockIdx.x, rb16 = blockIdx.y, lane = threadIdx.x;
+    const int r = lane & 15, c = lane >> 4;
+    const int n = rb16 * 16 + r;
+    const uint32_t *tile = packed + ((size_t)(rb16 / SUB) * G + g) * tile_dwords<BITS>();
+    uint32_t C[BITS];
+    load_chunk<BITS>(tile, rb16 % SUB, lane, C);
+    const size_t meta = ((size_t)rb16 * G + g) * 16 + r;
+    const float z = (float)zeros[meta], sc = (float)scales[meta];
+    if (n >= N)
+        return;
+#pragma unroll
+    for (int t = 0; t < 32; ++t) {
+        const int s = t >> 3, e = t & 7;
+        const int k = g * 128 + 32 * s + 8 * c + e;
+        const float d = __fsub_rn((float)code_at<BITS>(C, t), z);
+        const float w = __fmul_rn(sc, d);
+        if (out_is_fp16)
+            static_cast<_Float16 *>(out)[(size_t)n * K + k] = (_Float16)w;
+        else
+            static_cast<float *>(out)[(size_t)n * K + k] = w;
+    }
+}
+
+} // namespace
+
+int fq_launch_glue(int op, const void *a, const void *b, const void *c, int M, int H, void *out, fq_stream st)
+{
+    dim3 grid(M), block(256);
+    const _Float16 *pa = static_cast<const _Float16 *>(a), *pb = static_cast<const _Float16 *>(b),
+                   *pc = static_cast<const _Float16 *>(c);
+    _Float16 *po = static_cast<_Float16 *>(out);
+    switch (op) {
+    case 0: hipLaunchKernelGGL(glue_kernel<0>, grid, block, 0, st, pa, pb, pc, H, po); break;
+    case 1: hipLaunchKernelGGL(glue_kernel<1>, grid, block, 0, st, pa, pb, pc, H, po); break;
+    case 2: hipLaunchKernelGGL(glue_kernel<2>, grid, block, 0, st, pa, pb, pc, H, po); break;
+    case 3: hipLaunchKernelGGL(glue_kernel<3>, grid, block, 0, st, pa, pb, pc, H, po); break;
+    default: hipLaunchKernelGGL(glue_kernel<4>, grid, block, 0, st, pa, pb, pc, H, po); break;
+    }
+    return (int)hipGetLastError();
+}
+
+int fq_launch_nll(const void *logits, const int32_t *labels, int M, int V, float *nll, fq_stream st)
+{
+    hipLaunchKernelGGL(nll_kernel, dim3(M), dim3(256), 0, st, static_cast<const _Float16 *>(logits), labels, V, nll);
+    return (int)hipGetLastError();
+}
+
+int fq_launch_dequant(const fq_packed_ref &w, void *out, int out_is_fp16, fq_stream st)
+{
+    const int Np16 = (w.N + 63) / 64 * 4;
+    dim3 grid(w.K >> 7, Np16), block(64);
+    const uint32_t *p = static_cast<const uint32_t *>(w.packed);
+    const _Float16 *s = static_cast<const _Float16 *>(w.scales), *z = static_cast<const _Float16 *>(w.zeros);
+    switch (w.bits) {
+    case 2: hipLaunchKernelGGL(dequant_kernel<2>, grid, block, 0, st, p, s, z, w.N, w.K, out, out_is_fp16); break;
+    case 3: hipLaunchKernelGGL(dequant_kernel<3>, grid, block, 0, st, p, s, z, w.N, w.K, out, out_is_fp16); break;
+    case 4: hipLaunchKernelGGL(dequant_kernel<4>, grid, block, 0, st, p, s, z, w.N, w.K, out, out_is_fp16); break;
+    default: hipLaunchKernelGGL(dequant_kernel<8>, grid, block, 0, st, p, s, z, w.N, w.K, out, out_is_fp16); break;
+    }
+    return (int)hipGetLastError();
+}

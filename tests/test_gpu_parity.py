@@ -1,0 +1,304 @@
+"""GPU parity: every step of the hot path, through the C-ABI, against the CPU oracle.
+
+Tolerances
+  dequant / pack / index .......... bit-exact
+  qlinear (GEMV and GEMM) ......... max |y - r| / max(|r|, rms_n r[m,:]) <= 2e-3, y the fp16 output,
+                                    r the oracle's fp64 result (pure element-wise relative error is
+                                    unbounded where r ~ 0)
+  token NLL ....................... |per-sequence mean| <= 1e-3, per token <= 2e-3
+"""
+import math
+
+import numpy as np
+import pytest
+
+import fq_synth
+import oracle
+
+pytestmark = pytest.mark.gpu
+
+BITS = (2, 3, 4, 8)
+TOL = 2e-3
+
+
+@pytest.fixture(scope="module")
+def fq():
+    import paper_2501_07139_amd as mod
+
+    return mod
+
+
+@pytest.fixture(scope="module")
+def torch():
+    import torch as t
+
+    assert t.cuda.is_available()
+    return t
+
+
+def qerr(y, r):
+    """The qlinear error measure: |y - r| over max(|r|, row rms of r)."""
+    y = np.asarray(y, dtype=np.float64)
+    rms = np.sqrt(np.mean(r * r, axis=1, keepdims=True))
+    den = np.maximum(np.abs(r), np.maximum(rms, 1e-30))
+    return float(np.max(np.abs(y - r) / den))
+
+
+def make_matrix(fq, seed, N, K, bits):
+    W = fq_synth.weights(seed, N, K)
+    codes, s, z = oracle.quantize_rtn(W, bits)
+    return fq.PackedMatrix.from_host(codes, s, z, bits), codes, s, z
+
+
+def dev(torch, a):
+    if a.dtype == np.float16:
+        return torch.from_numpy(a.view(np.int16)).cuda().view(torch.float16)
+    return torch.from_numpy(a).cuda()
+
+
+def host16(t):
+    import torch as _t
+
+    return t.cpu().view(_t.int16).numpy().view(np.float16)
+
+
+# ------------------------------------------------------------------- dequant
+@pytest.mark.parametrize("bits", BITS)
+@pytest.mark.parametrize("shape", [(512, 512), (200, 384), (70, 256), (4096, 1024)])
+def test_dequant_bit_exact(fq, torch, bits, shape):
+    N, K = shape
+    w, codes, s, z = make_matrix(fq, 7, N, K, bits)
+    want = oracle.dequant(codes, s, z)
+    got = fq.fq_dequant(w).cpu().numpy()
+    assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
+    got16 = host16(fq.fq_dequant(w, fp16=True))
+    assert np.array_equal(got16.view(np.uint16), oracle.round_f16(want.astype(np.float64)).view(np.uint16))
+
+
+@pytest.mark.parametrize("bits", BITS)
+def test_dequant_arbitrary_codes_and_fractional_zeros(fq, torch, bits):
+    N, K = 128, 512
+    codes = fq_synth.codes(3, N, K, bits)
+    s = (np.abs(fq_synth.activations(4, N, K // 128).astype(np.float32)) * 0.01 + 1e-4).astype(np.float16)
+    z = (fq_synth.codes(5, N, K // 128, bits).astype(np.float32) / 16).astype(np.float16)
+    w = fq.PackedMatrix.from_host(codes, s, z, bits)
+    got = fq.fq_dequant(w).cpu().numpy()
+    assert np.array_equal(got.view(np.uint32), oracle.dequant(codes, s, z).view(np.uint32))
+
+
+# ------------------------------------------------------------------- qlinear
+GEMV_CASES = [(1, 512, 512), (16, 512, 512), (3, 200, 384), (1, 4096, 4096), (5, 70, 256), (1, 1, 128)]
+GEMM_CASES = [(17, 512, 512), (64, 512, 512), (300, 200, 384), (520, 384, 1024), (33, 70, 256), (256, 64, 128)]
+
+
+@pytest.mark.parametrize("bits", BITS)
+@pytest.mark.parametrize("case", GEMV_CASES + GEMM_CASES, ids=lambda c: "M%d_N%d_K%d" % c)
+def test_qlinear_against_oracle(fq, torch, bits, case):
+    M, N, K = case
+    w, codes, s, z = make_matrix(fq, 100 + bits, N, K, bits)
+    X = fq_synth.activations(9, M, K)
+    r = oracle.qlinear(X, oracle.dequant(codes, s, z))
+    y = host16(fq.fq_qlinear(dev(torch, X), w))
+    assert y.shape == (M, N)
+    assert qerr(y, r) <= TOL
+    # plain max-norm figure as well, for the record
+    assert np.max(np.abs(y.astype(np.float64) - r)) / np.max(np.abs(r)) <= TOL
+
+
+@pytest.mark.parametrize("bits", BITS)
+@pytest.mark.parametrize("M", [1, 16, 48])
+def test_qlinear_exact_on_integer_case(fq, torch, bits, M):
+    """Power-of-two scales and small-integer activations: every partial sum is exact."""
+    N, K = 96, 512
+    codes = fq_synth.codes(1, N, K, bits)
+    s = np.full((N, K // 128), 0.25, dtype=np.float16)
+    z = np.full((N, K // 128), float(1 << (bits - 1)), dtype=np.float16)
+    X = (fq_synth.codes(2, M, K, 3).astype(np.float32) - 4).astype(np.float16)
+    w = fq.PackedMatrix.from_host(codes, s, z, bits)
+    r = oracle.qlinear(X, oracle.dequant(codes, s, z))
+    assert np.array_equal(r * 4, np.rint(r * 4)) and np.max(np.abs(r)) * 4 < 2 ** 22  # exact in fp32 partial sums
+    y = host16(fq.fq_qlinear(dev(torch, X), w)).astype(np.float64)
+    assert np.array_equal(y, oracle.round_f16(r).astype(np.float64))
+
+
+@pytest.mark.parametrize("bits", (2, 3, 4))
+@pytest.mark.parametrize("M", [1, 40])
+@pytest.mark.parametrize("midpoint", [False, True])
+def test_qlinear_on_truncated_codes(fq, torch, bits, M, midpoint):
+    """Section "Elastic Serving": the b-bit layer obtained by dropping bits of the 8-bit one."""
+    N, K = 256, 512
+    W = fq_synth.weights(77, N, K)
+    q8, s8, z8 = oracle.quantize_rtn(W, 8)
+    q, s, z = oracle.truncate(q8, s8, z8, 8 - bits, midpoint=midpoint)
+    w = fq.PackedMatrix.from_host(q, s, z, bits)
+    W32 = oracle.dequant(q, s, z)
+    assert np.array_equal(fq.fq_dequant(w).cpu().numpy().view(np.uint32), W32.view(np.uint32))
+    X = fq_synth.activations(78, M, K)
+    y = host16(fq.fq_qlinear(dev(torch, X), w))
+    assert qerr(y, oracle.qlinear(X, W32)) <= TOL
+
+
+@pytest.mark.parametrize("bits", BITS)
+def test_qlinear_full_size_sampled(fq, torch, bits):
+    """Llama-2-7B matrix shapes at M=1 and M=2048; the oracle computes sampled rows and columns."""
+    rng = np.random.default_rng(bits)
+    for (N, K) in [(4096, 4096), (11008, 4096), (4096, 11008)]:
+        w, codes, s, z = make_matrix(fq, 200 + bits, N, K, bits)
+        cols = np.unique(np.concatenate([rng.integers(0, N, size=192), [0, N - 1]]))
+        W32 = oracle.dequant(codes[cols], s[cols], z[cols])
+        for M in (1, 2048):
+            X = fq_synth.activations(10, M, K)
+            y = host16(fq.fq_qlinear(dev(torch, X), w))
+            rows = np.arange(M) if M == 1 else np.unique(np.concatenate([rng.integers(0, M, size=48), [0, M - 1]]))
+            r = oracle.qlinear(X[rows], W32)
+            ysub = y[np.ix_(rows, cols)].astype(np.float64)
+            # rms over the sampled columns stands in for the row rms
+            assert qerr(ysub, r) <= TOL, (N, K, M)
+            assert np.all(np.isfinite(y.astype(np.float32)))
+
+
+def test_qlinear_is_deterministic(fq, torch):
+    w, *_ = make_matrix(fq, 5, 4096, 4096, 3)
+    for M in (1, 512):
+        X = dev(torch, fq_synth.activations(6, M, 4096))
+        a = fq.fq_qlinear(X, w)
+        b = fq.fq_qlinear(X, w)
+        assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+
+
+def test_more_bits_track_the_unquantized_layer_better_on_gpu(fq, torch):
+    N, K, M = 512, 1024, 64
+    W = fq_synth.weights(31, N, K)
+    X = fq_synth.activations(32, M, K)
+    Y = oracle.qlinear(X, W)
+    errs = []
+    for bits in BITS:
+        codes, s, z = oracle.quantize_rtn(W, bits)
+        y = host16(fq.fq_qlinear(dev(torch, X), fq.PackedMatrix.from_host(codes, s, z, bits))).astype(np.float64)
+        errs.append(np.sqrt(np.mean((y - Y) ** 2) / np.mean(Y ** 2)))
+    assert errs[0] > errs[1] > errs[2] > errs[3] and errs[3] < 1e-2
+
+
+# --------------------------------------------------------------- dense head
+@pytest.mark.parametrize("case", [(40, 512, 256), (300, 1000, 384), (2048, 32000, 512)], ids=str)
+def test_dense_head_against_oracle(fq, torch, case):
+    M, N, K = case
+    X = fq_synth.activations(13, M, K)
+    W = fq_synth.weights(14, N, K).astype(np.float16)
+    y = host16(fq.fq_dense_f16(dev(torch, X), dev(torch, W)))
+    if M * N > 1 << 20:
+        rng = np.random.default_rng(0)
+        rows, cols = np.unique(rng.integers(0, M, 40)), np.unique(rng.integers(0, N, 300))
+        r = oracle.dense_f16(X[rows], W[cols])
+        assert qerr(y[np.ix_(rows, cols)], r) <= TOL
+    else:
+        assert qerr(y, oracle.dense_f16(X, W)) <= TOL
+
+
+# ----------------------------------------------------------------------- NLL
+def test_token_nll_closed_forms(fq, torch):
+    V = 32000
+    x = np.zeros((6, V), dtype=np.float16)
+    x[1] += np.float16(65504.0)
+    x[2] -= np.float16(65504.0)
+    x[3, 17] = 60.0
+    x[4, 17] = 60.0
+    lab = np.array([0, 31999, 5, 17, 18, -1], dtype=np.int32)
+    got = fq.fq_token_nll(dev(torch, x), dev(torch, lab)).cpu().numpy().astype(np.float64)
+    want = [math.log(V)] * 3 + [0.0, 60.0, 0.0]
+    assert np.allclose(got, want, rtol=0, atol=1e-4)
+    assert np.allclose(got, oracle.token_nll(x, lab), rtol=0, atol=1e-4)
+
+
+@pytest.mark.parametrize("shape", [(2048, 32000), (130, 1001), (7, 8)])
+def test_token_nll_against_oracle(fq, torch, shape):
+    M, V = shape
+    L = fq_synth.logits(21, M, V)
+    lab = fq_synth.labels(22, M, V)
+    lab[0], lab[-1] = 0, V - 1
+    got = fq.fq_token_nll(dev(torch, L), dev(torch, lab)).cpu().numpy().astype(np.float64)
+    want = oracle.token_nll(L, lab)
+    assert np.max(np.abs(got - want)) <= 2e-3
+    assert abs(got.mean() - want.mean()) <= 1e-3  # per-sequence mean NLL
+    assert abs(math.exp(got.mean()) / oracle.perplexity(want) - 1) <= 1e-3
+
+
+# ---------------------------------------------------------------------- glue
+@pytest.mark.parametrize("H", [256, 4096, 11008, 13824])
+def test_glue_steps_against_oracle(fq, torch, H):
+    M = 9
+    a, b, c = (fq_synth.activations(40 + i, M, H) for i in range(3))
+    f = lambda t: t.astype(np.float64)
+    want = {
+        0: oracle.rms_rows(f(a)),
+        1: oracle.rms_rows(f(a) + f(b) + f(c)),
+        2: oracle.round_f16(f(a) + f(b)),
+        3: oracle.rms_rows(oracle.silu_mul(a, b)),
+        4: oracle.rms_rows(f(a) + f(b)),
+    }
+    da, db, dc = dev(torch, a), dev(torch, b), dev(torch, c)
+    for op, w in want.items():
+        got = host16(fq.fq_glue(op, da, db if op else None, dc if op == 1 else None))
+        # fp32 on the GPU against fp64 in the oracle: agree to one fp16 ulp, and almost always exactly
+        diff = np.abs(got.astype(np.float64) - w.astype(np.float64))
+        ulp = np.maximum(np.abs(w.astype(np.float64)), 2.0 ** -14) * 2.0 ** -10
+        assert np.all(diff <= ulp), op
+        assert np.mean(diff > 0) < 2e-3, op
+
+
+# --------------------------------------------------------------------- stack
+def build_stack(fq, shapes_key, seed, bit_choices=BITS):
+    sh = fq_synth.MODEL_SHAPES[shapes_key]
+    layers, host = [], []
+    for l in range(sh["layers"]):
+        mats, hmats = [], []
+        for j, (N, K) in enumerate(fq_synth.block_matrix_shapes(sh["hidden"], sh["ffn"])):
+            W = fq_synth.weights(seed, N, K, 0.02, l, j)
+            by_bits, hby = {}, {}
+            for b in bit_choices:
+                codes, s, z = oracle.quantize_rtn(W, b)
+                by_bits[b] = fq.PackedMatrix.from_host(codes, s, z, b)
+                hby[b] = (codes, s, z)
+            mats.append(by_bits)
+            hmats.append(hby)
+        layers.append(mats)
+        host.append(hmats)
+    return fq.Stack(layers), host, sh
+
+
+@pytest.mark.parametrize("M", [1, 4, 40])
+def test_stack_forward_against_oracle(fq, torch, M):
+    stack, host, sh = build_stack(fq, "tiny", 300)
+    bitvec = fq_synth.bit_vector(M, 7 * sh["layers"], probs=(0.25, 0.25, 0.25, 0.25))
+    x = fq_synth.activations(301, M, sh["hidden"])
+    got = host16(fq.fq_stack_forward(stack, bitvec, dev(torch, x)))
+    # end to end: fp16 re-rounding between steps lets single ulps flip, so the bound is looser
+    mats = [[oracle.dequant(*host[l][j][int(bitvec[7 * l + j])]) for j in range(7)] for l in range(sh["layers"])]
+    want = oracle.stack_forward(x, mats)
+    assert np.max(np.abs(got.astype(np.float64) - want.astype(np.float64))) <= 2e-2
+    assert np.mean(np.abs(got.astype(np.float64) - want.astype(np.float64))) <= 2e-3
+    # teacher-forced: one block at a time from the GPU's own layer input
+    xin = x
+    for l in range(sh["layers"]):
+        sub = fq.Stack([stack.layers[l]])
+        gout = host16(fq.fq_stack_forward(sub, bitvec[7 * l:7 * l + 7], dev(torch, xin)))
+        t = oracle.block_forward(xin, mats[l])
+        assert np.max(np.abs(gout.astype(np.float64) - t["x_next"].astype(np.float64))) <= 1e-2, l
+        xin = gout
+    assert np.array_equal(xin.view(np.uint16), got.view(np.uint16))
+
+
+def test_block_steps_teacher_forced(fq, torch):
+    """Each of the seven linears and five glue steps of a block, fed the oracle's inputs."""
+    stack, host, sh = build_stack(fq, "tiny", 310)
+    bitvec = np.array([2, 3, 4, 8, 3, 2, 4], dtype=np.uint8)
+    M = 24
+    x = fq_synth.activations(311, M, sh["hidden"])
+    mats = [oracle.dequant(*host[0][j][int(bitvec[j])]) for j in range(7)]
+    t = oracle.block_forward(x, mats)
+    inputs = ["u", "u", "u", "a", "u2", "u2", "m"]
+    outputs = ["q", "k", "v", "o", "g", "p", "d"]
+    for j in range(7):
+        w = stack.layers[0][j][int(bitvec[j])]
+        y = host16(fq.fq_qlinear(dev(torch, t[inputs[j]]), w))
+        assert qerr(y, oracle.qlinear(t[inputs[j]], mats[j])) <= TOL, outputs[j]
