@@ -1,0 +1,247 @@
+#!/usr/bin/env python3
+"""Benchmark of the mixed-bit quantized-linear hot path on one MI355X.
+
+Workload ("llama2-7b-block"): the seven linears of one Llama-2-7B-shaped decoder
+block (q/k/v/o 4096x4096, gate/up 4096->11008, down 11008->4096), group 128,
+per-matrix bit-widths drawn (seeded) from {2,3,4,8}, random-init weights,
+synthetic activations.  One step is one pass of the whole path:
+
+  leg A (calibration forward, M=2048): block forward through fq_stack_forward,
+        fp16 head 4096->32000, fused token NLL;
+  leg B (decode, M=1): the block's GEMVs through fq_stack_forward over DECODE_LAYERS
+        distinct copies of the block, so that every pass streams more packed bytes
+        than the 256 MB last-level cache holds (cold weights, launch gaps included).
+
+Prints ONE JSON line.  `value` is the algorithmic TFLOP/s of the whole step;
+`legs` breaks it down (GEMM TFLOP/s at M=2048, GEMV GB/s at M=1, NLL GB/s);
+`roofline` is for the kernel the step spends most of its time in (the dequant-GEMM);
+`cpu_baseline` times the CPU oracle on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import numpy as np  # noqa: E402
+
+HIDDEN, FFN, VOCAB = 4096, 11008, 32000
+M_FWD = 2048
+DECODE_LAYERS = 8
+PEAK_MFMA_F16_TFLOPS = 2516.6  # 256 CU x 4096 flop/clk x 2.4 GHz
+PEAK_HBM_GBPS = 8000.0
+SEED = 1
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
+    ap.add_argument("--cpu-rows", type=int, default=16, help="rows of leg A the oracle is timed on")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (no collectives, no sharding); run with --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import fq_synth
+    import paper_2501_07139_amd as fq
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+
+    def to_dev(a):
+        if a.dtype == np.float16:
+            return torch.from_numpy(a.view(np.int16)).to(dev).view(torch.float16)
+        return torch.from_numpy(a).to(dev)
+
+    # ---------------------------------------------------------------- inputs
+    shapes = fq_synth.block_matrix_shapes(HIDDEN, FFN)
+    bitvec = fq_synth.bit_vector(SEED, 7, probs=(0.25, 0.25, 0.25, 0.25))
+    host_q = []   # per matrix: (codes, scales, zeros) at the selected bit-width (for the oracle leg)
+    block = []    # per matrix: {bits: PackedMatrix}
+    for j, (N, K) in enumerate(shapes):
+        W = fq_synth.weights(SEED, N, K, 0.02, 0, j)
+        b = int(bitvec[j])
+        codes, s, z = fq.fq_quantize_rtn(W, b)
+        host_q.append((codes, s, z))
+        block.append({b: fq.PackedMatrix.from_host(codes, s, z, b)})
+        del W
+    # decode leg: DECODE_LAYERS distinct device copies of the block
+    dec_layers = [block]
+    for _ in range(DECODE_LAYERS - 1):
+        dec_layers.append([{b: fq.PackedMatrix(w.packed.clone(), w.scales.clone(), w.zeros.clone(), w.N, w.K, b)
+                            for b, w in m.items()} for m in block])
+    stack_fwd = fq.Stack([block])
+    stack_dec = fq.Stack(dec_layers)
+    bitvec_dec = np.tile(bitvec, DECODE_LAYERS)
+
+    x_fwd_h = fq_synth.activations(SEED, M_FWD, HIDDEN)
+    x_fwd = to_dev(x_fwd_h)
+    x_dec = to_dev(fq_synth.activations(SEED + 1, 1, HIDDEN))
+    head_h = fq_synth.weights(SEED, VOCAB, HIDDEN, 0.02, 99).astype(np.float16)
+    head = to_dev(head_h)
+    labels_h = fq_synth.labels(SEED, M_FWD, VOCAB)
+    labels = to_dev(labels_h)
+
+    ws_fwd = torch.empty(fq.fq_stack_workspace_bytes(M_FWD, HIDDEN, FFN), dtype=torch.uint8, device=dev)
+    ws_dec = torch.empty(fq.fq_stack_workspace_bytes(1, HIDDEN, FFN), dtype=torch.uint8, device=dev)
+    h_out = torch.empty_like(x_fwd)
+    d_out = torch.empty_like(x_dec)
+    logits = torch.empty((M_FWD, VOCAB), dtype=torch.float16, device=dev)
+    nll = torch.empty(M_FWD, dtype=torch.float32, device=dev)
+
+    def leg_a():
+        fq.fq_stack_forward(stack_fwd, bitvec, x_fwd, out=h_out, workspace=ws_fwd)
+        fq.fq_dense_f16(h_out, head, out=logits)
+        fq.fq_token_nll(logits, labels, out=nll)
+
+    def leg_b():
+        fq.fq_stack_forward(stack_dec, bitvec_dec, x_dec, out=d_out, workspace=ws_dec)
+
+    def step():
+        leg_a()
+        leg_b()
+
+    # ------------------------------------------------------- algorithmic work
+    gemm_flops = sum(2.0 * M_FWD * N * K for N, K in shapes)
+    head_flops = 2.0 * M_FWD * VOCAB * HIDDEN
+    gemv_flops = DECODE_LAYERS * sum(2.0 * N * K for N, K in shapes)
+    block_bytes = sum(block[j][int(bitvec[j])].nbytes + 2 * K + 2 * N for j, (N, K) in enumerate(shapes))
+    gemv_bytes = DECODE_LAYERS * block_bytes
+    nll_bytes = 2.0 * M_FWD * VOCAB
+    step_flops = gemm_flops + head_flops + gemv_flops
+
+    # ------------------------------------------------------------ timed steps
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    # per-leg and per-kernel durations with events on the launch stream
+    def timed(fn, reps):
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / reps  # ms
+
+    reps = max(5, args.steps)
+    ms_fwd_block = timed(lambda: fq.fq_stack_forward(stack_fwd, bitvec, x_fwd, out=h_out, workspace=ws_fwd), reps)
+    ms_head = timed(lambda: fq.fq_dense_f16(h_out, head, out=logits), reps)
+    ms_nll = timed(lambda: fq.fq_token_nll(logits, labels, out=nll), reps)
+    ms_dec = timed(leg_b, reps)
+
+    # the dominant kernel: dequant-GEMM launches of leg A, one by one
+    kernels = []
+    u = fq.fq_glue(0, x_fwd)
+    mm = torch.empty((M_FWD, FFN), dtype=torch.float16, device=dev).normal_()
+    gemm_ms_total = 0.0
+    for j, (N, K) in enumerate(shapes):
+        w = block[j][int(bitvec[j])]
+        xin = mm if K == FFN else u
+        out = torch.empty((M_FWD, N), dtype=torch.float16, device=dev)
+        ms = timed(lambda: fq.fq_qlinear(xin, w, out=out), reps)
+        gemm_ms_total += ms
+        kernels.append({"matrix": fq_synth.MATRIX_NAMES[j], "N": N, "K": K, "bits": int(bitvec[j]),
+                        "ms": round(ms, 4), "tflops": round(2.0 * M_FWD * N * K / ms / 1e9, 1)})
+    gemm_tflops = gemm_flops / gemm_ms_total / 1e9
+
+    # GEMV kernels of leg B, rotating over the distinct copies (cold)
+    gemv_ms_total = 0.0
+    gemv_kernels = []
+    for j, (N, K) in enumerate(shapes):
+        ws = [dec_layers[l][j][int(bitvec[j])] for l in range(DECODE_LAYERS)]
+        xin = torch.empty((1, K), dtype=torch.float16, device=dev).normal_()
+        out = torch.empty((1, N), dtype=torch.float16, device=dev)
+
+        def rot():
+            for w in ws:
+                fq.fq_qlinear(xin, w, out=out)
+
+        ms = timed(rot, reps) / DECODE_LAYERS
+        gemv_ms_total += ms
+        nbytes = ws[0].nbytes + 2 * K + 2 * N
+        gemv_kernels.append({"matrix": fq_synth.MATRIX_NAMES[j], "N": N, "K": K, "bits": int(bitvec[j]),
+                             "us": round(ms * 1e3, 2), "GBps": round(nbytes / ms / 1e6, 1)})
+
+    result = {
+        "metric": "dequant-GEMM TFLOP/s (M=2048) with dequant-GEMV GB/s (M=1) in legs, one Llama-2-7B block",
+        "value": round(step_flops / ms_per_step / 1e9, 2),
+        "unit": "TFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f16",
+        "data": "synthetic",
+        "config": {"workload": "llama2-7b-block: 7 linears, bits %s, group 128, M=2048 forward + fp16 head + NLL,"
+                               " M=1 decode over %d block copies" % ("/".join(map(str, bitvec)), DECODE_LAYERS),
+                   "hidden": HIDDEN, "ffn": FFN, "vocab": VOCAB, "seed": SEED},
+        "legs": {
+            "gemm_m2048": {"tflops_kernels": round(gemm_tflops, 1),
+                           "tflops_block_forward": round(gemm_flops / ms_fwd_block / 1e9, 1),
+                           "ms_block_forward": round(ms_fwd_block, 4), "frac_mfma_peak": round(gemm_tflops / PEAK_MFMA_F16_TFLOPS, 4)},
+            "head_m2048": {"tflops": round(head_flops / ms_head / 1e9, 1), "ms": round(ms_head, 4)},
+            "nll": {"GBps": round(nll_bytes / ms_nll / 1e6, 1), "ms": round(ms_nll, 4)},
+            "gemv_m1": {"GBps_kernels_cold": round(block_bytes / gemv_ms_total / 1e6, 1),
+                        "GBps_stack_decode": round(gemv_bytes / ms_dec / 1e6, 1),
+                        "ms_stack_decode": round(ms_dec, 4), "layers": DECODE_LAYERS,
+                        "frac_hbm_peak": round(block_bytes / gemv_ms_total / 1e6 / PEAK_HBM_GBPS, 4)},
+        },
+        "kernels": {"gemm": kernels, "gemv": gemv_kernels},
+        "roofline": {"bound": "mfma", "achieved": round(gemm_tflops, 1), "peak": PEAK_MFMA_F16_TFLOPS,
+                     "unit": "TFLOP/s", "frac": round(gemm_tflops / PEAK_MFMA_F16_TFLOPS, 4), "traffic": None,
+                     "kernel": "gemm_kernel (dequant-GEMM, M=2048, the 7 block matrices)"},
+    }
+
+    # ---------------------------------------------------- CPU oracle baseline
+    if not args.no_cpu_baseline:
+        import oracle
+
+        rows = max(1, min(args.cpu_rows, M_FWD))
+        t0 = time.perf_counter()
+        mats = [oracle.dequant(*host_q[j]) for j in range(7)]
+        t = oracle.block_forward(x_fwd_h[:rows], mats)
+        lg = oracle.round_f16(oracle.dense_f16(t["x_next"], head_h))
+        ref_nll = oracle.token_nll(lg, labels_h[:rows])
+        cpu_s = time.perf_counter() - t0
+        cpu_flops = rows / M_FWD * (gemm_flops + head_flops)
+        result["cpu_baseline"] = {"value": round(cpu_flops / cpu_s / 1e12, 6), "unit": "TFLOP/s",
+                                  "cores": oracle.threads(), "kind": "oracle",
+                                  "sample": "leg A on %d of %d rows (dequant + block forward + head + NLL), %.1f s"
+                                            % (rows, M_FWD, cpu_s)}
+        got = nll[:rows].cpu().numpy().astype(np.float64)
+        result["parity"] = {"nll_mean_abs_diff_sample": round(float(abs(got.mean() - ref_nll.mean())), 6)}
+
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

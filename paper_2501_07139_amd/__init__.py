@@ -43,6 +43,10 @@ class fq_layer(ctypes.Structure):
 def _load() -> ctypes.CDLL:
     if not os.path.exists(LIB_PATH):
         raise ImportError(f"{LIB_PATH} is not built; run `python -m paper_2501_07139_amd.build`")
+    # PyTorch ships its own HIP runtime (same soname).  Import it first so that libfq binds to
+    # that one copy; two runtimes in one process do not both see the device.
+    import torch  # noqa: F401
+
     lib = ctypes.CDLL(LIB_PATH)
     vp, ci, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
     sig = {

@@ -152,7 +152,7 @@ __global__ __launch_bounds__(256) void nll_kernel(const _Float16 *__restrict__ l
         float m = pm[0], s = ps[0];
         for (int w = 1; w < 4; ++w)
             lse_merge(m, s, pm[w], ps[w]);
-        nll[row] = logf(s) + m - (float)l[label];
+        nll[row] = logf(s) + (m - (float)l[label]); // difference first: exact for fp16 inputs
     }
 }
 
