@@ -3,42 +3,204 @@
 //
 // Scoring one candidate hybrid model means a full forward of the calibration
 // sequences (FlexQuant, arXiv 2501.07139, Algorithm 1, calibrationEval), which is
-// a dense contraction: packed weights are unpacked and dequantized once per
-// workgroup tile into fp16 operand fragments in LDS and consumed by 16x16x32
-// MFMA with fp32 accumulation.
+// a dense contraction, so it runs on the matrix cores: 16x16x32 fp16 MFMA with
+// fp32 accumulation.
 //
-// Tile: BM activation rows x BN weight rows x one group of 128 k per step,
-// 256 threads = 2x2 wavefronts.  The weight fragments sit in LDS in operand
-// order (every read and write is a contiguous 1 KiB per wavefront); the
-// activation tile is row-major with its 16-byte chunks XOR-swizzled by row so
-// that both the coalesced global->LDS copy and the operand reads are free of
-// bank conflicts.
+// Quantized kernel.  Workgroup tile: BM=128 activation rows x BN=128 weight rows,
+// one group of 128 k per iteration, 256 threads = 4 wavefronts side by side along
+// N (each 128 x 32), two workgroups resident per CU.  The packed format stores a lane's 32 weights of a group as
+// the A operands of four consecutive MFMA k-steps, so every wavefront loads its
+// own packed chunks straight from global memory into registers (1 KiB contiguous
+// per load), dequantizes them there and feeds the matrix core: weights never
+// touch LDS and are unpacked once per workgroup.  Activations are shared by the
+// four wavefronts through a double-buffered LDS tile, row-major with 16-byte
+// chunks XOR-swizzled by row so that the coalesced global->LDS copy and the
+// operand reads are both free of bank conflicts.  Loads for group g+1 are issued
+// before the MFMAs of group g; one barrier per iteration.
+//
+// Dense kernel (head): both operands staged through LDS, same MFMA shape.
 #include "fq_device.h"
 #include "fq_internal.h"
 
 namespace {
 
-constexpr int DENSE = 16; // BITS value selecting the fp16 weight path
+// ------------------------------------------------------------ quantized GEMM
+constexpr int QBM = 128, QNB = 2, QBN = 64 * QNB, QMB = QBM / 16; // per wave: QNB weight blocks x QMB activation blocks
 
-template <int BITS, int BM, int BN>
-__global__ __launch_bounds__(256) void gemm_kernel(const _Float16 *__restrict__ x, int M,
-                                                   const uint32_t *__restrict__ packed,
-                                                   const _Float16 *__restrict__ scales,
-                                                   const _Float16 *__restrict__ zeros,
-                                                   int N, int K, _Float16 *__restrict__ out)
+template <int BITS>
+struct WChunk {
+    uint32_t c[BITS];
+    _Float16 scale, zero;
+};
+
+template <int BITS>
+__device__ __forceinline__ void load_wchunk(WChunk<BITS> &w, const uint32_t *__restrict__ packed,
+                                            const _Float16 *__restrict__ scales,
+                                            const _Float16 *__restrict__ zeros, int rb16, int Np16, int G, int g,
+                                            int lane)
 {
-    constexpr int WM = BM / 2, WN = BN / 2; // per-wave tile
+    constexpr int SUB = Fmt<BITS>::SUB;
+    if (rb16 < Np16) {
+        const uint32_t *tile = packed + ((size_t)(rb16 / SUB) * G + g) * tile_dwords<BITS>();
+        load_chunk<BITS>(tile, rb16 % SUB, lane, w.c);
+        const size_t meta = ((size_t)rb16 * G + g) * 16 + (lane & 15);
+        w.scale = scales[meta];
+        w.zero = zeros[meta];
+    } else {
+#pragma unroll
+        for (int i = 0; i < BITS; ++i)
+            w.c[i] = 0;
+        w.scale = (_Float16)0.f;
+        w.zero = (_Float16)0.f;
+    }
+}
+
+// Two workgroups per CU (two wavefronts per SIMD): a single wavefront cannot keep the matrix pipe
+// busy, and two independent workgroups overlap one's unpack/copy phase with the other's MFMAs.
+template <int BITS>
+__global__ __launch_bounds__(256, 2) void qgemm_kernel(const _Float16 *__restrict__ x, int M,
+                                                       const uint32_t *__restrict__ packed,
+                                                       const _Float16 *__restrict__ scales,
+                                                       const _Float16 *__restrict__ zeros, int N, int K,
+                                                       _Float16 *__restrict__ out)
+{
+    __shared__ h8 Xs[2][QBM * 16]; // chunk ch of row r at r*16 + (ch ^ (r & 15))
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int m0 = blockIdx.y * QBM, n0 = blockIdx.x * QBN;
+    const int G = K >> 7;
+    const int Np16 = ((N + 63) / 64 * 64) >> 4;
+    const int rb0 = (n0 >> 4) + wave * QNB; // first sixteen-row weight block of this wave
+
+    // activation copy: 8 chunks of 16 bytes per thread per group; row = tid/16 + 16*i, chunk = tid%16
+    const int xrow = tid >> 4, xch = tid & 15;
+    const int xdst = xrow * 16 + (xch ^ (xrow & 15));
+    const _Float16 *xsrc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+        xsrc[i] = x + (size_t)min(m0 + xrow + 16 * i, M - 1) * K + xch * 8;
+
+    f4 acc[QNB][QMB];
+#pragma unroll
+    for (int i = 0; i < QNB; ++i)
+#pragma unroll
+        for (int j = 0; j < QMB; ++j)
+            acc[i][j] = f4{0.f, 0.f, 0.f, 0.f};
+
+    h8 xr[8];
+    WChunk<BITS> wc[QNB];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+        xr[i] = *reinterpret_cast<const h8 *>(xsrc[i]);
+#pragma unroll
+    for (int i = 0; i < QNB; ++i)
+        load_wchunk<BITS>(wc[i], packed, scales, zeros, rb0 + i, Np16, G, 0, lane);
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+        Xs[0][xdst + 256 * i] = xr[i];
+    __syncthreads();
+
+    for (int g = 0; g < G; ++g) {
+        const int cur = g & 1;
+        // dequantize this group's weights into operands: (code - zero) * scale
+        h8 a[QNB][4];
+#pragma unroll
+        for (int i = 0; i < QNB; ++i) {
+            h2 q[16];
+            unpack_codes<BITS>(wc[i].c, q);
+            const h2 z2 = {wc[i].zero, wc[i].zero}, s2 = {wc[i].scale, wc[i].scale};
+#pragma unroll
+            for (int p = 0; p < 16; ++p)
+                q[p] = (q[p] - z2) * s2;
+#pragma unroll
+            for (int s = 0; s < 4; ++s)
+                a[i][s] = make_h8(q[4 * s], q[4 * s + 1], q[4 * s + 2], q[4 * s + 3]);
+        }
+        // prefetch the next group
+        const bool more = g + 1 < G;
+        if (more) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                xr[i] = *reinterpret_cast<const h8 *>(xsrc[i] + (size_t)(g + 1) * 128);
+#pragma unroll
+            for (int i = 0; i < QNB; ++i)
+                load_wchunk<BITS>(wc[i], packed, scales, zeros, rb0 + i, Np16, G, g + 1, lane);
+        }
+        // contraction
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            h8 b[QMB];
+#pragma unroll
+            for (int j = 0; j < QMB; ++j) {
+                const int row = j * 16 + (lane & 15), ch = 4 * s + (lane >> 4);
+                b[j] = Xs[cur][row * 16 + (ch ^ (row & 15))];
+            }
+#pragma unroll
+            for (int i = 0; i < QNB; ++i)
+#pragma unroll
+                for (int j = 0; j < QMB; ++j)
+                    acc[i][j] = mfma16x16x32(a[i][s], b[j], acc[i][j]);
+        }
+        if (more) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                Xs[cur ^ 1][xdst + 256 * i] = xr[i];
+        }
+        __syncthreads();
+    }
+
+    // store: lane holds m = lane%16 and n = 4*(lane/16) + v of each 16x16 block
+#pragma unroll
+    for (int j = 0; j < QMB; ++j) {
+        const int m = m0 + j * 16 + (lane & 15);
+        if (m >= M)
+            continue;
+#pragma unroll
+        for (int i = 0; i < QNB; ++i) {
+            const int n = (rb0 + i) * 16 + 4 * (lane >> 4);
+            _Float16 *o = out + (size_t)m * N + n;
+            if (n + 3 < N && (N & 3) == 0) {
+                h4 v = {(_Float16)acc[i][j][0], (_Float16)acc[i][j][1], (_Float16)acc[i][j][2], (_Float16)acc[i][j][3]};
+                *reinterpret_cast<h4 *>(o) = v;
+            } else {
+#pragma unroll
+                for (int v = 0; v < 4; ++v)
+                    if (n + v < N)
+                        o[v] = (_Float16)acc[i][j][v];
+            }
+        }
+    }
+}
+
+template <int BITS>
+int launch_q(const void *x, int M, const fq_packed_ref &w, void *out, fq_stream st)
+{
+    dim3 grid((w.N + QBN - 1) / QBN, (M + QBM - 1) / QBM), block(256);
+    hipLaunchKernelGGL(qgemm_kernel<BITS>, grid, block, 0, st, static_cast<const _Float16 *>(x), M,
+                       static_cast<const uint32_t *>(w.packed), static_cast<const _Float16 *>(w.scales),
+                       static_cast<const _Float16 *>(w.zeros), w.N, w.K, static_cast<_Float16 *>(out));
+    return (int)hipGetLastError();
+}
+
+// ---------------------------------------------------------------- dense GEMM
+// Tile BM x BN, 2x2 wavefronts, both operands row-major in LDS with the same swizzle.
+template <int BM, int BN>
+__global__ __launch_bounds__(256) void dgemm_kernel(const _Float16 *__restrict__ x, int M,
+                                                    const _Float16 *__restrict__ W, int N, int K,
+                                                    _Float16 *__restrict__ out)
+{
+    constexpr int WM = BM / 2, WN = BN / 2;
     constexpr int MB = WM / 16, NB = WN / 16;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    h8 *Xs = reinterpret_cast<h8 *>(smem);                // [BM][16 chunks], chunk ch of row r at r*16 + (ch ^ (r & 15))
-    h8 *Ws = reinterpret_cast<h8 *>(smem + BM * 256);     // packed: [BN/16][4 k-steps][64 lanes]; dense: like Xs
+    h8 *Xs = reinterpret_cast<h8 *>(smem);
+    h8 *Ws = reinterpret_cast<h8 *>(smem + BM * 256);
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
     const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
     const int G = K >> 7;
-    const int Np16 = ((N + 63) / 64 * 64) >> 4; // sixteen-row blocks that exist in the packed buffer
 
     f4 acc[NB][MB];
 #pragma unroll
@@ -48,70 +210,28 @@ __global__ __launch_bounds__(256) void gemm_kernel(const _Float16 *__restrict__ 
             acc[i][j] = f4{0.f, 0.f, 0.f, 0.f};
 
     for (int g = 0; g < G; ++g) {
-        // ---- activations: BM rows x 16 chunks of 8 halves
 #pragma unroll
         for (int i = 0; i < BM * 16 / 256; ++i) {
             const int idx = tid + 256 * i;
             const int row = idx >> 4, ch = idx & 15;
-            const int mrow = min(m0 + row, M - 1);
             Xs[row * 16 + (ch ^ (row & 15))] =
-                *reinterpret_cast<const h8 *>(x + (size_t)mrow * K + g * 128 + ch * 8);
+                *reinterpret_cast<const h8 *>(x + (size_t)min(m0 + row, M - 1) * K + g * 128 + ch * 8);
         }
-        // ---- weights
-        if constexpr (BITS == DENSE) {
-            const _Float16 *Wd = reinterpret_cast<const _Float16 *>(packed);
 #pragma unroll
-            for (int i = 0; i < BN * 16 / 256; ++i) {
-                const int idx = tid + 256 * i;
-                const int row = idx >> 4, ch = idx & 15;
-                const int nrow = min(n0 + row, N - 1);
-                Ws[row * 16 + (ch ^ (row & 15))] =
-                    *reinterpret_cast<const h8 *>(Wd + (size_t)nrow * K + g * 128 + ch * 8);
-            }
-        } else {
-            constexpr int SUB = Fmt<BITS>::SUB;
-            constexpr int TILE = tile_dwords<BITS>();
-#pragma unroll
-            for (int i = 0; i < BN / 64; ++i) {
-                const int blk = wave + 4 * i;        // sixteen-row block inside the tile
-                const int rb16 = (n0 >> 4) + blk;    // ... and in the matrix
-                h8 *dst = Ws + (blk * 4) * 64 + lane;
-                if (rb16 < Np16) {
-                    const int sr = rb16 / SUB, u = rb16 % SUB;
-                    const uint32_t *tile = packed + ((size_t)sr * G + g) * TILE;
-                    uint32_t C[BITS];
-                    load_chunk<BITS>(tile, u, lane, C);
-                    const size_t meta = ((size_t)rb16 * G + g) * 16 + (lane & 15);
-                    const _Float16 z = zeros[meta], sc = scales[meta];
-                    h2 q[16];
-                    unpack_codes<BITS>(C, q);
-                    const h2 z2 = {z, z}, s2 = {sc, sc};
-#pragma unroll
-                    for (int p = 0; p < 16; ++p)
-                        q[p] = (q[p] - z2) * s2;
-#pragma unroll
-                    for (int s = 0; s < 4; ++s)
-                        dst[s * 64] = make_h8(q[4 * s], q[4 * s + 1], q[4 * s + 2], q[4 * s + 3]);
-                } else {
-#pragma unroll
-                    for (int s = 0; s < 4; ++s)
-                        dst[s * 64] = h8{0, 0, 0, 0, 0, 0, 0, 0};
-                }
-            }
+        for (int i = 0; i < BN * 16 / 256; ++i) {
+            const int idx = tid + 256 * i;
+            const int row = idx >> 4, ch = idx & 15;
+            Ws[row * 16 + (ch ^ (row & 15))] =
+                *reinterpret_cast<const h8 *>(W + (size_t)min(n0 + row, N - 1) * K + g * 128 + ch * 8);
         }
         __syncthreads();
-        // ---- contraction over the four k-steps of the group
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
             h8 a[NB], b[MB];
 #pragma unroll
             for (int i = 0; i < NB; ++i) {
-                if constexpr (BITS == DENSE) {
-                    const int row = wn * WN + i * 16 + (lane & 15), ch = 4 * s + (lane >> 4);
-                    a[i] = Ws[row * 16 + (ch ^ (row & 15))];
-                } else {
-                    a[i] = Ws[((wn * NB + i) * 4 + s) * 64 + lane];
-                }
+                const int row = wn * WN + i * 16 + (lane & 15), ch = 4 * s + (lane >> 4);
+                a[i] = Ws[row * 16 + (ch ^ (row & 15))];
             }
 #pragma unroll
             for (int j = 0; j < MB; ++j) {
@@ -127,7 +247,6 @@ __global__ __launch_bounds__(256) void gemm_kernel(const _Float16 *__restrict__ 
         __syncthreads();
     }
 
-    // ---- store: lane holds m = lane%16, n = 4*(lane/16) + v of each 16x16 block
 #pragma unroll
     for (int j = 0; j < MB; ++j) {
         const int m = m0 + wm * WM + j * 16 + (lane & 15);
@@ -150,12 +269,23 @@ __global__ __launch_bounds__(256) void gemm_kernel(const _Float16 *__restrict__ 
     }
 }
 
-template <int BITS, int BM, int BN>
-int launch(const void *x, int M, const void *packed, const void *scales, const void *zeros, int N, int K,
-           void *out, fq_stream st)
+} // namespace
+
+int fq_launch_gemm(const void *x, int M, const fq_packed_ref &w, void *out, fq_stream st)
 {
+    switch (w.bits) {
+    case 2: return launch_q<2>(x, M, w, out, st);
+    case 3: return launch_q<3>(x, M, w, out, st);
+    case 4: return launch_q<4>(x, M, w, out, st);
+    default: return launch_q<8>(x, M, w, out, st);
+    }
+}
+
+int fq_launch_dense(const void *x, int M, const void *W, int N, int K, void *out, fq_stream st)
+{
+    constexpr int BM = 256, BN = 128;
     constexpr size_t lds = (size_t)(BM + BN) * 256;
-    auto kern = gemm_kernel<BITS, BM, BN>;
+    auto kern = dgemm_kernel<BM, BN>;
     static bool configured = false;
     if (!configured) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -166,25 +296,6 @@ int launch(const void *x, int M, const void *packed, const void *scales, const v
     }
     dim3 grid((N + BN - 1) / BN, (M + BM - 1) / BM), block(256);
     hipLaunchKernelGGL(kern, grid, block, lds, st, static_cast<const _Float16 *>(x), M,
-                       static_cast<const uint32_t *>(packed), static_cast<const _Float16 *>(scales),
-                       static_cast<const _Float16 *>(zeros), N, K, static_cast<_Float16 *>(out));
+                       static_cast<const _Float16 *>(W), N, K, static_cast<_Float16 *>(out));
     return (int)hipGetLastError();
-}
-
-} // namespace
-
-int fq_launch_gemm(const void *x, int M, const fq_packed_ref &w, void *out, fq_stream st)
-{
-    constexpr int BM = 256, BN = 128;
-    switch (w.bits) {
-    case 2: return launch<2, BM, BN>(x, M, w.packed, w.scales, w.zeros, w.N, w.K, out, st);
-    case 3: return launch<3, BM, BN>(x, M, w.packed, w.scales, w.zeros, w.N, w.K, out, st);
-    case 4: return launch<4, BM, BN>(x, M, w.packed, w.scales, w.zeros, w.N, w.K, out, st);
-    default: return launch<8, BM, BN>(x, M, w.packed, w.scales, w.zeros, w.N, w.K, out, st);
-    }
-}
-
-int fq_launch_dense(const void *x, int M, const void *W, int N, int K, void *out, fq_stream st)
-{
-    return launch<DENSE, 256, 128>(x, M, W, nullptr, nullptr, N, K, out, st);
 }
