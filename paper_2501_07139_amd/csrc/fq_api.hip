@@ -40,6 +40,20 @@ int qlinear_checked(const void *x, int M, const fq_packed_ref &w, void *out, fq_
     return check_hip(e, "fq_qlinear launch");
 }
 
+// Linears that read the same input: one launch on the decode path, one call each otherwise.
+int qlinear_group(const void *x, int M, const fq_packed_ref *w, void *const *outs, int count, fq_stream st)
+{
+    bool fuse = M <= 16 && count > 1;
+    for (int i = 0; i < count && fuse; ++i)
+        fuse = fq_gemv_can_stream(M, w[i].K, w[i].bits);
+    if (fuse)
+        return check_hip(fq_launch_gemv_multi(x, M, w, outs, count, st), "fq_qlinear (fused decode launch)");
+    for (int i = 0; i < count; ++i)
+        if (int rc = qlinear_checked(x, M, w[i], outs[i], st))
+            return rc;
+    return FQ_OK;
+}
+
 constexpr int kMaxGlueH = 16384;
 
 size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
@@ -172,15 +186,14 @@ extern "C" int fq_stack_forward(const fq_layer *layers, int L, const uint8_t *bi
     if ((rc = (call)) != FQ_OK) \
         return rc
         FQ_STEP(check_hip(fq_launch_glue(0, xcur, nullptr, nullptr, M, H, u, st), "glue rms"));
-        FQ_STEP(qlinear_checked(u, M, sel[0], q, st));
-        FQ_STEP(qlinear_checked(u, M, sel[1], k, st));
-        FQ_STEP(qlinear_checked(u, M, sel[2], v, st));
+        void *const qkv[3] = {q, k, v};
+        FQ_STEP(qlinear_group(u, M, &sel[0], qkv, 3, st));
         FQ_STEP(check_hip(fq_launch_glue(1, q, k, v, M, H, a, st), "glue rms(q+k+v)"));
         FQ_STEP(qlinear_checked(a, M, sel[3], o, st));
         FQ_STEP(check_hip(fq_launch_glue(2, xcur, o, nullptr, M, H, x1, st), "glue add"));
         FQ_STEP(check_hip(fq_launch_glue(0, x1, nullptr, nullptr, M, H, u2, st), "glue rms"));
-        FQ_STEP(qlinear_checked(u2, M, sel[4], g, st));
-        FQ_STEP(qlinear_checked(u2, M, sel[5], p, st));
+        void *const gp[2] = {g, p};
+        FQ_STEP(qlinear_group(u2, M, &sel[4], gp, 2, st));
         FQ_STEP(check_hip(fq_launch_glue(3, g, p, nullptr, M, F, mm, st), "glue rms(silu*mul)"));
         FQ_STEP(qlinear_checked(mm, M, sel[6], d, st));
         FQ_STEP(check_hip(fq_launch_glue(4, x1, d, nullptr, M, H, xnext, st), "glue rms(add)"));

@@ -148,87 +148,72 @@ __device__ __forceinline__ void unpack_codes(const uint32_t (&C)[BITS], h2 (&q)[
     }
 }
 
-// Half chunks: the dwords of a lane's chunk that hold k-steps 2*kh and 2*kh+1
-// (kh = 0 or 1, uniform across the wavefront).  For 2, 4 and 8 bits these are
-// separate dwords, so a wave that works on one half of each group loads only
-// those; a 3-bit chunk is loaded whole.
+// Biased pairs without the fix-up: h[4*s + v] reads, as two fp16 numbers,
+// 1024 + code * 2^pair_shift(4*s + v) for elements 2v and 2v+1 of k-step s.  The
+// streaming kernel feeds these to the matrix core as they are and removes the
+// bias once per group instead of once per weight.
 template <int BITS>
-struct HalfChunk { static constexpr int DW = (BITS == 3) ? 3 : BITS / 2; };
-
-template <int BITS>
-__device__ __forceinline__ void load_half_chunk(const uint32_t *tile, int u, int lane, int kh,
-                                                uint32_t (&H)[HalfChunk<BITS>::DW])
+__host__ __device__ constexpr int pair_shift(int p)
 {
-    if constexpr (BITS == 4) {
-        u2v v = *reinterpret_cast<const u2v *>(tile + lane * 4 + 2 * kh);
-        H[0] = v.x; H[1] = v.y;
-    } else if constexpr (BITS == 8) {
-        u4v v = *reinterpret_cast<const u4v *>(tile + kh * 256 + lane * 4);
-        H[0] = v.x; H[1] = v.y; H[2] = v.z; H[3] = v.w;
-    } else if constexpr (BITS == 2) {
-        H[0] = tile[lane * 4 + 2 * u + kh];
-    } else {
-#pragma unroll
-        for (int i = 0; i < 3; ++i)
-            H[i] = tile[lane_dword(3 * u + i, lane)];
+    if (BITS == 4)
+        return (p & 1) ? 4 : 0;
+    if (BITS == 2) {
+        constexpr int sh[8] = {0, 2, 4, 6, 8, 0, 2, 4};
+        return sh[p & 7];
     }
+    if (BITS == 3) {
+        constexpr int sh[5] = {0, 3, 6, 0, 3};
+        return p == 15 ? 0 : sh[p % 5];
+    }
+    return 0;
 }
 
-// Exact codes of the 16 weights of a half chunk: q[4*j + v] holds elements 2v, 2v+1 of k-step 2*kh + j.
 template <int BITS>
-__device__ __forceinline__ void unpack_half(const uint32_t (&H)[HalfChunk<BITS>::DW], int kh, h2 (&q)[8])
+__device__ __forceinline__ void extract_biased(const uint32_t (&C)[BITS], uint32_t (&h)[16])
 {
     if constexpr (BITS == 4) {
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const uint32_t w = H[j], t = w >> 8;
-            q[4 * j + 0] = debias<0>((w & 0x000f000fu) | FQ_EXP1024);
-            q[4 * j + 1] = debias<4>((w & 0x00f000f0u) | FQ_EXP1024);
-            q[4 * j + 2] = debias<0>((t & 0x000f000fu) | FQ_EXP1024);
-            q[4 * j + 3] = debias<4>((t & 0x00f000f0u) | FQ_EXP1024);
+        for (int s = 0; s < 4; ++s) {
+            const uint32_t w = C[s], t = w >> 8;
+            h[4 * s + 0] = (w & 0x000f000fu) | FQ_EXP1024;
+            h[4 * s + 1] = (w & 0x00f000f0u) | FQ_EXP1024;
+            h[4 * s + 2] = (t & 0x000f000fu) | FQ_EXP1024;
+            h[4 * s + 3] = (t & 0x00f000f0u) | FQ_EXP1024;
         }
     } else if constexpr (BITS == 2) {
-        const uint32_t w = H[0], t = w >> 10;
-        q[0] = debias<0>((w & 0x00030003u) | FQ_EXP1024);
-        q[1] = debias<2>((w & 0x000c000cu) | FQ_EXP1024);
-        q[2] = debias<4>((w & 0x00300030u) | FQ_EXP1024);
-        q[3] = debias<6>((w & 0x00c000c0u) | FQ_EXP1024);
-        q[4] = debias<8>((w & 0x03000300u) | FQ_EXP1024);
-        q[5] = debias<0>((t & 0x00030003u) | FQ_EXP1024);
-        q[6] = debias<2>((t & 0x000c000cu) | FQ_EXP1024);
-        q[7] = debias<4>((t & 0x00300030u) | FQ_EXP1024);
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const uint32_t w = C[j], t = w >> 10;
+            h[8 * j + 0] = (w & 0x00030003u) | FQ_EXP1024;
+            h[8 * j + 1] = (w & 0x000c000cu) | FQ_EXP1024;
+            h[8 * j + 2] = (w & 0x00300030u) | FQ_EXP1024;
+            h[8 * j + 3] = (w & 0x00c000c0u) | FQ_EXP1024;
+            h[8 * j + 4] = (w & 0x03000300u) | FQ_EXP1024;
+            h[8 * j + 5] = (t & 0x00030003u) | FQ_EXP1024;
+            h[8 * j + 6] = (t & 0x000c000cu) | FQ_EXP1024;
+            h[8 * j + 7] = (t & 0x00300030u) | FQ_EXP1024;
+        }
     } else if constexpr (BITS == 8) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const uint32_t w = H[j];
-            q[2 * j + 0] = debias<0>((w & 0x00ff00ffu) | FQ_EXP1024);
-            q[2 * j + 1] = debias<0>(((w >> 8) & 0x00ff00ffu) | FQ_EXP1024);
+        for (int j = 0; j < 8; ++j) {
+            const uint32_t w = C[j];
+            h[2 * j + 0] = (w & 0x00ff00ffu) | FQ_EXP1024;
+            h[2 * j + 1] = ((w >> 8) & 0x00ff00ffu) | FQ_EXP1024;
         }
     } else {
-        if (kh == 0) { // pairs 0..7: five in dword 0, three in dword 1
-            const uint32_t w = H[0], t = w >> 9, w1 = H[1];
-            q[0] = debias<0>((w & 0x00070007u) | FQ_EXP1024);
-            q[1] = debias<3>((w & 0x00380038u) | FQ_EXP1024);
-            q[2] = debias<6>((w & 0x01c001c0u) | FQ_EXP1024);
-            q[3] = debias<0>((t & 0x00070007u) | FQ_EXP1024);
-            q[4] = debias<3>((t & 0x00380038u) | FQ_EXP1024);
-            q[5] = debias<0>((w1 & 0x00070007u) | FQ_EXP1024);
-            q[6] = debias<3>((w1 & 0x00380038u) | FQ_EXP1024);
-            q[7] = debias<6>((w1 & 0x01c001c0u) | FQ_EXP1024);
-        } else { // pairs 8..15: two in dword 1, five in dword 2, one spread over bits 15/31
-            const uint32_t t1 = H[1] >> 9, w = H[2], t = w >> 9;
-            q[0] = debias<0>((t1 & 0x00070007u) | FQ_EXP1024);
-            q[1] = debias<3>((t1 & 0x00380038u) | FQ_EXP1024);
-            q[2] = debias<0>((w & 0x00070007u) | FQ_EXP1024);
-            q[3] = debias<3>((w & 0x00380038u) | FQ_EXP1024);
-            q[4] = debias<6>((w & 0x01c001c0u) | FQ_EXP1024);
-            q[5] = debias<0>((t & 0x00070007u) | FQ_EXP1024);
-            q[6] = debias<3>((t & 0x00380038u) | FQ_EXP1024);
-            uint32_t sp = ((H[0] >> 15) & 0x00010001u) | FQ_EXP1024;
-            sp |= (H[1] >> 14) & 0x00020002u;
-            sp |= (H[2] >> 13) & 0x00040004u;
-            q[7] = debias<0>(sp);
+#pragma unroll
+        for (int d = 0; d < 3; ++d) {
+            const uint32_t w = C[d], t = w >> 9;
+            h[5 * d + 0] = (w & 0x00070007u) | FQ_EXP1024;
+            h[5 * d + 1] = (w & 0x00380038u) | FQ_EXP1024;
+            h[5 * d + 2] = (w & 0x01c001c0u) | FQ_EXP1024;
+            h[5 * d + 3] = (t & 0x00070007u) | FQ_EXP1024;
+            h[5 * d + 4] = (t & 0x00380038u) | FQ_EXP1024;
         }
+        uint32_t sp = ((C[0] >> 15) & 0x00010001u) | FQ_EXP1024;
+        sp |= (C[1] >> 14) & 0x00020002u;
+        sp |= (C[2] >> 13) & 0x00040004u;
+        h[15] = sp;
     }
 }
 
@@ -239,6 +224,12 @@ __device__ __forceinline__ h8 make_h8(h2 a, h2 b, h2 c, h2 d)
     r[0] = a[0]; r[1] = a[1]; r[2] = b[0]; r[3] = b[1];
     r[4] = c[0]; r[5] = c[1]; r[6] = d[0]; r[7] = d[1];
     return r;
+}
+
+__device__ __forceinline__ h8 make_h8_bits(uint32_t a, uint32_t b, uint32_t c, uint32_t d)
+{
+    const u4v v = {a, b, c, d};
+    return __builtin_bit_cast(h8, v);
 }
 
 __device__ __forceinline__ f4 mfma16x16x32(h8 a, h8 b, f4 c)

@@ -23,6 +23,9 @@ struct fq_packed_ref {
 // Launchers.  Arguments are validated by the callers in fq_api.hip; each returns a hipError_t as int.
 int fq_launch_dequant(const fq_packed_ref &w, void *out, int out_is_fp16, fq_stream st);
 int fq_launch_gemv(const void *x, int M, const fq_packed_ref &w, void *out, fq_stream st);
+// Streaming decode kernel: up to three matrices that share x and K in one launch (M <= 16).
+bool fq_gemv_can_stream(int M, int K, int bits);
+int fq_launch_gemv_multi(const void *x, int M, const fq_packed_ref *w, void *const *outs, int count, fq_stream st);
 int fq_launch_gemm(const void *x, int M, const fq_packed_ref &w, void *out, fq_stream st);
 int fq_launch_dense(const void *x, int M, const void *W, int N, int K, void *out, fq_stream st);
 int fq_launch_glue(int op, const void *a, const void *b, const void *c, int M, int H, void *out, fq_stream st);
