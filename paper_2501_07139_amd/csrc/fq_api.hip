@@ -40,20 +40,6 @@ int qlinear_checked(const void *x, int M, const fq_packed_ref &w, void *out, fq_
     return check_hip(e, "fq_qlinear launch");
 }
 
-// Linears that read the same input: one launch on the decode path, one call each otherwise.
-int qlinear_group(const void *x, int M, const fq_packed_ref *w, void *const *outs, int count, fq_stream st)
-{
-    bool fuse = M <= 16 && count > 1;
-    for (int i = 0; i < count && fuse; ++i)
-        fuse = fq_gemv_can_stream(M, w[i].K, w[i].bits);
-    if (fuse)
-        return check_hip(fq_launch_gemv_multi(x, M, w, outs, count, st), "fq_qlinear (fused decode launch)");
-    for (int i = 0; i < count; ++i)
-        if (int rc = qlinear_checked(x, M, w[i], outs[i], st))
-            return rc;
-    return FQ_OK;
-}
-
 constexpr int kMaxGlueH = 16384;
 
 size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
@@ -173,6 +159,13 @@ extern "C" int fq_stack_forward(const fq_layer *layers, int L, const uint8_t *bi
          *x1 = ws + 6 * hb, *u2 = ws + 7 * hb, *d = ws + 8 * hb, *xc = ws + 9 * hb;
     void *g = ws + 10 * hb, *p = ws + 10 * hb + fb, *mm = ws + 10 * hb + 2 * fb;
 
+    // Decode (M <= 16): four launches per block.  q/k/v and gate/up share a launch each, and every
+    // row-wise step is folded into the input staging of the linear that consumes it.
+    bool decode = M <= 16;
+    for (int l = 0; l < L && decode; ++l)
+        for (int j = 0; j < 7; ++j)
+            decode = decode && fq_gemv_can_stream(M, layers[l].m[j].K, bitvec[7 * l + j]);
+
     const void *xcur = x_in;
     for (int l = 0; l < L; ++l) {
         for (int j = 0; j < 7; ++j) {
@@ -181,19 +174,38 @@ extern "C" int fq_stack_forward(const fq_layer *layers, int L, const uint8_t *bi
             sel[j] = fq_packed_ref{mx.packed[bi], mx.scales[bi], mx.zeros[bi], mx.N, mx.K, bits};
         }
         void *xnext = (l == L - 1) ? x_out : xc;
+        void *const qkv[3] = {q, k, v};
+        void *const gp[2] = {g, p};
         int rc;
 #define FQ_STEP(call) \
     if ((rc = (call)) != FQ_OK) \
         return rc
+        if (decode) {
+            // the previous block's x_next = rms(x1 + d) is produced (into xc) by this block's first launch
+            const fq_gemv_input in_qkv = (l == 0) ? fq_gemv_input{x_in, nullptr, nullptr, nullptr, 1}
+                                                  : fq_gemv_input{x1, d, nullptr, xc, 5};
+            if (l > 0)
+                xcur = xc;
+            FQ_STEP(check_hip(fq_launch_gemv_multi(in_qkv, M, &sel[0], qkv, 3, st), "decode q/k/v"));
+            FQ_STEP(check_hip(fq_launch_gemv_multi(fq_gemv_input{q, k, v, nullptr, 2}, M, &sel[3], &o, 1, st),
+                              "decode o"));
+            FQ_STEP(check_hip(fq_launch_gemv_multi(fq_gemv_input{xcur, o, nullptr, x1, 3}, M, &sel[4], gp, 2, st),
+                              "decode gate/up"));
+            FQ_STEP(check_hip(fq_launch_gemv_multi(fq_gemv_input{g, p, nullptr, nullptr, 4}, M, &sel[6], &d, 1, st),
+                              "decode down"));
+            if (l == L - 1)
+                FQ_STEP(check_hip(fq_launch_glue(4, x1, d, nullptr, M, H, x_out, st), "glue rms(add)"));
+            continue;
+        }
         FQ_STEP(check_hip(fq_launch_glue(0, xcur, nullptr, nullptr, M, H, u, st), "glue rms"));
-        void *const qkv[3] = {q, k, v};
-        FQ_STEP(qlinear_group(u, M, &sel[0], qkv, 3, st));
+        for (int j = 0; j < 3; ++j)
+            FQ_STEP(qlinear_checked(u, M, sel[j], qkv[j], st));
         FQ_STEP(check_hip(fq_launch_glue(1, q, k, v, M, H, a, st), "glue rms(q+k+v)"));
         FQ_STEP(qlinear_checked(a, M, sel[3], o, st));
         FQ_STEP(check_hip(fq_launch_glue(2, xcur, o, nullptr, M, H, x1, st), "glue add"));
         FQ_STEP(check_hip(fq_launch_glue(0, x1, nullptr, nullptr, M, H, u2, st), "glue rms"));
-        void *const gp[2] = {g, p};
-        FQ_STEP(qlinear_group(u2, M, &sel[4], gp, 2, st));
+        for (int j = 0; j < 2; ++j)
+            FQ_STEP(qlinear_checked(u2, M, sel[4 + j], gp[j], st));
         FQ_STEP(check_hip(fq_launch_glue(3, g, p, nullptr, M, F, mm, st), "glue rms(silu*mul)"));
         FQ_STEP(qlinear_checked(mm, M, sel[6], d, st));
         FQ_STEP(check_hip(fq_launch_glue(4, x1, d, nullptr, M, H, xnext, st), "glue rms(add)"));

@@ -89,6 +89,15 @@ __device__ __forceinline__ uint32_t code_at(const uint32_t (&C)[BITS], int t)
 // ---------------------------------------------------------------------------
 #define FQ_EXP1024 0x64006400u
 
+// The exponent pattern held in a scalar register: with only the mask as a literal, (w & mask) | exp
+// is a single and-or instruction.
+__device__ __forceinline__ uint32_t exp1024_reg()
+{
+    uint32_t e = FQ_EXP1024;
+    asm volatile("" : "+s"(e));
+    return e;
+}
+
 template <int P>
 __device__ __forceinline__ h2 debias(uint32_t biased)
 {
@@ -101,47 +110,48 @@ __device__ __forceinline__ h2 debias(uint32_t biased)
 template <int BITS>
 __device__ __forceinline__ void unpack_codes(const uint32_t (&C)[BITS], h2 (&q)[16])
 {
+    const uint32_t EXP = exp1024_reg();
     if constexpr (BITS == 4) {
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
             const uint32_t w = C[s], t = w >> 8;
-            q[4 * s + 0] = debias<0>((w & 0x000f000fu) | FQ_EXP1024);
-            q[4 * s + 1] = debias<4>((w & 0x00f000f0u) | FQ_EXP1024);
-            q[4 * s + 2] = debias<0>((t & 0x000f000fu) | FQ_EXP1024);
-            q[4 * s + 3] = debias<4>((t & 0x00f000f0u) | FQ_EXP1024);
+            q[4 * s + 0] = debias<0>((w & 0x000f000fu) | EXP);
+            q[4 * s + 1] = debias<4>((w & 0x00f000f0u) | EXP);
+            q[4 * s + 2] = debias<0>((t & 0x000f000fu) | EXP);
+            q[4 * s + 3] = debias<4>((t & 0x00f000f0u) | EXP);
         }
     } else if constexpr (BITS == 2) {
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
             const uint32_t w = C[j], t = w >> 10;
-            q[8 * j + 0] = debias<0>((w & 0x00030003u) | FQ_EXP1024);
-            q[8 * j + 1] = debias<2>((w & 0x000c000cu) | FQ_EXP1024);
-            q[8 * j + 2] = debias<4>((w & 0x00300030u) | FQ_EXP1024);
-            q[8 * j + 3] = debias<6>((w & 0x00c000c0u) | FQ_EXP1024);
-            q[8 * j + 4] = debias<8>((w & 0x03000300u) | FQ_EXP1024);
-            q[8 * j + 5] = debias<0>((t & 0x00030003u) | FQ_EXP1024);
-            q[8 * j + 6] = debias<2>((t & 0x000c000cu) | FQ_EXP1024);
-            q[8 * j + 7] = debias<4>((t & 0x00300030u) | FQ_EXP1024);
+            q[8 * j + 0] = debias<0>((w & 0x00030003u) | EXP);
+            q[8 * j + 1] = debias<2>((w & 0x000c000cu) | EXP);
+            q[8 * j + 2] = debias<4>((w & 0x00300030u) | EXP);
+            q[8 * j + 3] = debias<6>((w & 0x00c000c0u) | EXP);
+            q[8 * j + 4] = debias<8>((w & 0x03000300u) | EXP);
+            q[8 * j + 5] = debias<0>((t & 0x00030003u) | EXP);
+            q[8 * j + 6] = debias<2>((t & 0x000c000cu) | EXP);
+            q[8 * j + 7] = debias<4>((t & 0x00300030u) | EXP);
         }
     } else if constexpr (BITS == 8) {
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             const uint32_t w = C[j];
             // bytes 0 and 2 form one pair, bytes 1 and 3 the next
-            q[2 * j + 0] = debias<0>((w & 0x00ff00ffu) | FQ_EXP1024);
-            q[2 * j + 1] = debias<0>(((w >> 8) & 0x00ff00ffu) | FQ_EXP1024);
+            q[2 * j + 0] = debias<0>((w & 0x00ff00ffu) | EXP);
+            q[2 * j + 1] = debias<0>(((w >> 8) & 0x00ff00ffu) | EXP);
         }
     } else {
 #pragma unroll
         for (int d = 0; d < 3; ++d) {
             const uint32_t w = C[d], t = w >> 9;
-            q[5 * d + 0] = debias<0>((w & 0x00070007u) | FQ_EXP1024);
-            q[5 * d + 1] = debias<3>((w & 0x00380038u) | FQ_EXP1024);
-            q[5 * d + 2] = debias<6>((w & 0x01c001c0u) | FQ_EXP1024);
-            q[5 * d + 3] = debias<0>((t & 0x00070007u) | FQ_EXP1024);
-            q[5 * d + 4] = debias<3>((t & 0x00380038u) | FQ_EXP1024);
+            q[5 * d + 0] = debias<0>((w & 0x00070007u) | EXP);
+            q[5 * d + 1] = debias<3>((w & 0x00380038u) | EXP);
+            q[5 * d + 2] = debias<6>((w & 0x01c001c0u) | EXP);
+            q[5 * d + 3] = debias<0>((t & 0x00070007u) | EXP);
+            q[5 * d + 4] = debias<3>((t & 0x00380038u) | EXP);
         }
-        uint32_t sp = ((C[0] >> 15) & 0x00010001u) | FQ_EXP1024;
+        uint32_t sp = ((C[0] >> 15) & 0x00010001u) | EXP;
         sp |= (C[1] >> 14) & 0x00020002u;
         sp |= (C[2] >> 13) & 0x00040004u;
         q[15] = debias<0>(sp);
@@ -171,46 +181,47 @@ __host__ __device__ constexpr int pair_shift(int p)
 template <int BITS>
 __device__ __forceinline__ void extract_biased(const uint32_t (&C)[BITS], uint32_t (&h)[16])
 {
+    const uint32_t EXP = exp1024_reg();
     if constexpr (BITS == 4) {
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
             const uint32_t w = C[s], t = w >> 8;
-            h[4 * s + 0] = (w & 0x000f000fu) | FQ_EXP1024;
-            h[4 * s + 1] = (w & 0x00f000f0u) | FQ_EXP1024;
-            h[4 * s + 2] = (t & 0x000f000fu) | FQ_EXP1024;
-            h[4 * s + 3] = (t & 0x00f000f0u) | FQ_EXP1024;
+            h[4 * s + 0] = (w & 0x000f000fu) | EXP;
+            h[4 * s + 1] = (w & 0x00f000f0u) | EXP;
+            h[4 * s + 2] = (t & 0x000f000fu) | EXP;
+            h[4 * s + 3] = (t & 0x00f000f0u) | EXP;
         }
     } else if constexpr (BITS == 2) {
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
             const uint32_t w = C[j], t = w >> 10;
-            h[8 * j + 0] = (w & 0x00030003u) | FQ_EXP1024;
-            h[8 * j + 1] = (w & 0x000c000cu) | FQ_EXP1024;
-            h[8 * j + 2] = (w & 0x00300030u) | FQ_EXP1024;
-            h[8 * j + 3] = (w & 0x00c000c0u) | FQ_EXP1024;
-            h[8 * j + 4] = (w & 0x03000300u) | FQ_EXP1024;
-            h[8 * j + 5] = (t & 0x00030003u) | FQ_EXP1024;
-            h[8 * j + 6] = (t & 0x000c000cu) | FQ_EXP1024;
-            h[8 * j + 7] = (t & 0x00300030u) | FQ_EXP1024;
+            h[8 * j + 0] = (w & 0x00030003u) | EXP;
+            h[8 * j + 1] = (w & 0x000c000cu) | EXP;
+            h[8 * j + 2] = (w & 0x00300030u) | EXP;
+            h[8 * j + 3] = (w & 0x00c000c0u) | EXP;
+            h[8 * j + 4] = (w & 0x03000300u) | EXP;
+            h[8 * j + 5] = (t & 0x00030003u) | EXP;
+            h[8 * j + 6] = (t & 0x000c000cu) | EXP;
+            h[8 * j + 7] = (t & 0x00300030u) | EXP;
         }
     } else if constexpr (BITS == 8) {
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             const uint32_t w = C[j];
-            h[2 * j + 0] = (w & 0x00ff00ffu) | FQ_EXP1024;
-            h[2 * j + 1] = ((w >> 8) & 0x00ff00ffu) | FQ_EXP1024;
+            h[2 * j + 0] = (w & 0x00ff00ffu) | EXP;
+            h[2 * j + 1] = ((w >> 8) & 0x00ff00ffu) | EXP;
         }
     } else {
 #pragma unroll
         for (int d = 0; d < 3; ++d) {
             const uint32_t w = C[d], t = w >> 9;
-            h[5 * d + 0] = (w & 0x00070007u) | FQ_EXP1024;
-            h[5 * d + 1] = (w & 0x00380038u) | FQ_EXP1024;
-            h[5 * d + 2] = (w & 0x01c001c0u) | FQ_EXP1024;
-            h[5 * d + 3] = (t & 0x00070007u) | FQ_EXP1024;
-            h[5 * d + 4] = (t & 0x00380038u) | FQ_EXP1024;
+            h[5 * d + 0] = (w & 0x00070007u) | EXP;
+            h[5 * d + 1] = (w & 0x00380038u) | EXP;
+            h[5 * d + 2] = (w & 0x01c001c0u) | EXP;
+            h[5 * d + 3] = (t & 0x00070007u) | EXP;
+            h[5 * d + 4] = (t & 0x00380038u) | EXP;
         }
-        uint32_t sp = ((C[0] >> 15) & 0x00010001u) | FQ_EXP1024;
+        uint32_t sp = ((C[0] >> 15) & 0x00010001u) | EXP;
         sp |= (C[1] >> 14) & 0x00020002u;
         sp |= (C[2] >> 13) & 0x00040004u;
         h[15] = sp;

@@ -23,9 +23,17 @@ struct fq_packed_ref {
 // Launchers.  Arguments are validated by the callers in fq_api.hip; each returns a hipError_t as int.
 int fq_launch_dequant(const fq_packed_ref &w, void *out, int out_is_fp16, fq_stream st);
 int fq_launch_gemv(const void *x, int M, const fq_packed_ref &w, void *out, fq_stream st);
-// Streaming decode kernel: up to three matrices that share x and K in one launch (M <= 16).
+// Streaming decode kernel: up to three matrices that share their input and K in one launch (M <= 16).
+// The input is x = f(a, b, c), fp16 [M,K] each, with the block's row-wise glue folded in:
+//   mode 0: a   1: rms(a)   2: rms(a+b+c)   3: aux = a+b, rms(aux)   4: rms(silu(a)*b)   5: aux = rms(a+b), rms(aux)
+struct fq_gemv_input {
+    const void *a, *b, *c;
+    void *aux;
+    int mode;
+};
 bool fq_gemv_can_stream(int M, int K, int bits);
-int fq_launch_gemv_multi(const void *x, int M, const fq_packed_ref *w, void *const *outs, int count, fq_stream st);
+int fq_launch_gemv_multi(const fq_gemv_input &src, int M, const fq_packed_ref *w, void *const *outs, int count,
+                         fq_stream st);
 int fq_launch_gemm(const void *x, int M, const fq_packed_ref &w, void *out, fq_stream st);
 int fq_launch_dense(const void *x, int M, const void *W, int N, int K, void *out, fq_stream st);
 int fq_launch_glue(int op, const void *a, const void *b, const void *c, int M, int H, void *out, fq_stream st);
