@@ -18,7 +18,8 @@
 // operand reads are both free of bank conflicts.  Loads for group g+1 are issued
 // before the MFMAs of group g; one barrier per iteration.
 //
-// Dense kernel (head): both operands staged through LDS, same MFMA shape.
+// The unquantized head runs the same kernel: its fp16 weights are read from the row-major matrix
+// directly into the operand registers (sixteen rows by 64 contiguous bytes per load).
 #include "fq_device.h"
 #include "fq_internal.h"
 
@@ -27,10 +28,18 @@ namespace {
 // ------------------------------------------------------------ quantized GEMM
 constexpr int QBM = 128, QNB = 2, QBN = 64 * QNB, QMB = QBM / 16; // per wave: QNB weight blocks x QMB activation blocks
 
+constexpr int DENSE = 16; // BITS value of the unquantized fp16 weight path (the vocabulary head)
+
 template <int BITS>
 struct WChunk {
     uint32_t c[BITS];
     _Float16 scale, zero;
+};
+
+// fp16 weights: a lane's operands of the four k-steps, read straight from the row-major matrix
+template <>
+struct WChunk<DENSE> {
+    h8 f[4];
 };
 
 template <int BITS>
@@ -39,6 +48,16 @@ __device__ __forceinline__ void load_wchunk(WChunk<BITS> &w, const uint32_t *__r
                                             const _Float16 *__restrict__ zeros, int rb16, int Np16, int G, int g,
                                             int lane)
 {
+    if constexpr (BITS == DENSE) {
+        // packed is the fp16 matrix [N,K]; Np16 carries N here.  Rows past the end re-read the last row.
+        const _Float16 *W = reinterpret_cast<const _Float16 *>(packed);
+        const int row = min(rb16 * 16 + (lane & 15), Np16 - 1);
+        const _Float16 *src = W + (size_t)row * (G * 128) + g * 128 + 8 * (lane >> 4);
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+            w.f[s] = *reinterpret_cast<const h8 *>(src + 32 * s);
+        return;
+    } else {
     constexpr int SUB = Fmt<BITS>::SUB;
     if (rb16 < Np16) {
         const uint32_t *tile = packed + ((size_t)(rb16 / SUB) * G + g) * tile_dwords<BITS>();
@@ -52,6 +71,7 @@ __device__ __forceinline__ void load_wchunk(WChunk<BITS> &w, const uint32_t *__r
             w.c[i] = 0;
         w.scale = (_Float16)0.f;
         w.zero = (_Float16)0.f;
+    }
     }
 }
 
@@ -70,7 +90,7 @@ __global__ __launch_bounds__(256, 2) void qgemm_kernel(const _Float16 *__restric
     const int lane = tid & 63, wave = tid >> 6;
     const int m0 = blockIdx.y * QBM, n0 = blockIdx.x * QBN;
     const int G = K >> 7;
-    const int Np16 = ((N + 63) / 64 * 64) >> 4;
+    const int Np16 = BITS == DENSE ? N : ((N + 63) / 64 * 64) >> 4; // sixteen-row blocks present (dense: rows)
     const int rb0 = (n0 >> 4) + wave * QNB; // first sixteen-row weight block of this wave
 
     // activation copy: 8 chunks of 16 bytes per thread per group; row = tid/16 + 16*i, chunk = tid%16
@@ -107,15 +127,21 @@ __global__ __launch_bounds__(256, 2) void qgemm_kernel(const _Float16 *__restric
         h8 a[QNB][4];
 #pragma unroll
         for (int i = 0; i < QNB; ++i) {
-            h2 q[16];
-            unpack_codes<BITS>(wc[i].c, q);
-            const h2 z2 = {wc[i].zero, wc[i].zero}, s2 = {wc[i].scale, wc[i].scale};
+            if constexpr (BITS == DENSE) {
 #pragma unroll
-            for (int p = 0; p < 16; ++p)
-                q[p] = (q[p] - z2) * s2;
+                for (int s = 0; s < 4; ++s)
+                    a[i][s] = wc[i].f[s];
+            } else {
+                h2 q[16];
+                unpack_codes<BITS>(wc[i].c, q);
+                const h2 z2 = {wc[i].zero, wc[i].zero}, s2 = {wc[i].scale, wc[i].scale};
 #pragma unroll
-            for (int s = 0; s < 4; ++s)
-                a[i][s] = make_h8(q[4 * s], q[4 * s + 1], q[4 * s + 2], q[4 * s + 3]);
+                for (int p = 0; p < 16; ++p)
+                    q[p] = (q[p] - z2) * s2;
+#pragma unroll
+                for (int s = 0; s < 4; ++s)
+                    a[i][s] = make_h8(q[4 * s], q[4 * s + 1], q[4 * s + 2], q[4 * s + 3]);
+            }
         }
         // prefetch the next group
         const bool more = g + 1 < G;
@@ -183,92 +209,6 @@ int launch_q(const void *x, int M, const fq_packed_ref &w, void *out, fq_stream 
     return (int)hipGetLastError();
 }
 
-// ---------------------------------------------------------------- dense GEMM
-// Tile BM x BN, 2x2 wavefronts, both operands row-major in LDS with the same swizzle.
-template <int BM, int BN>
-__global__ __launch_bounds__(256) void dgemm_kernel(const _Float16 *__restrict__ x, int M,
-                                                    const _Float16 *__restrict__ W, int N, int K,
-                                                    _Float16 *__restrict__ out)
-{
-    constexpr int WM = BM / 2, WN = BN / 2;
-    constexpr int MB = WM / 16, NB = WN / 16;
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    h8 *Xs = reinterpret_cast<h8 *>(smem);
-    h8 *Ws = reinterpret_cast<h8 *>(smem + BM * 256);
-
-    const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
-    const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
-    const int G = K >> 7;
-
-    f4 acc[NB][MB];
-#pragma unroll
-    for (int i = 0; i < NB; ++i)
-#pragma unroll
-        for (int j = 0; j < MB; ++j)
-            acc[i][j] = f4{0.f, 0.f, 0.f, 0.f};
-
-    for (int g = 0; g < G; ++g) {
-#pragma unroll
-        for (int i = 0; i < BM * 16 / 256; ++i) {
-            const int idx = tid + 256 * i;
-            const int row = idx >> 4, ch = idx & 15;
-            Xs[row * 16 + (ch ^ (row & 15))] =
-                *reinterpret_cast<const h8 *>(x + (size_t)min(m0 + row, M - 1) * K + g * 128 + ch * 8);
-        }
-#pragma unroll
-        for (int i = 0; i < BN * 16 / 256; ++i) {
-            const int idx = tid + 256 * i;
-            const int row = idx >> 4, ch = idx & 15;
-            Ws[row * 16 + (ch ^ (row & 15))] =
-                *reinterpret_cast<const h8 *>(W + (size_t)min(n0 + row, N - 1) * K + g * 128 + ch * 8);
-        }
-        __syncthreads();
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            h8 a[NB], b[MB];
-#pragma unroll
-            for (int i = 0; i < NB; ++i) {
-                const int row = wn * WN + i * 16 + (lane & 15), ch = 4 * s + (lane >> 4);
-                a[i] = Ws[row * 16 + (ch ^ (row & 15))];
-            }
-#pragma unroll
-            for (int j = 0; j < MB; ++j) {
-                const int row = wm * WM + j * 16 + (lane & 15), ch = 4 * s + (lane >> 4);
-                b[j] = Xs[row * 16 + (ch ^ (row & 15))];
-            }
-#pragma unroll
-            for (int i = 0; i < NB; ++i)
-#pragma unroll
-                for (int j = 0; j < MB; ++j)
-                    acc[i][j] = mfma16x16x32(a[i], b[j], acc[i][j]);
-        }
-        __syncthreads();
-    }
-
-#pragma unroll
-    for (int j = 0; j < MB; ++j) {
-        const int m = m0 + wm * WM + j * 16 + (lane & 15);
-        if (m >= M)
-            continue;
-#pragma unroll
-        for (int i = 0; i < NB; ++i) {
-            const int n = n0 + wn * WN + i * 16 + 4 * (lane >> 4);
-            _Float16 *o = out + (size_t)m * N + n;
-            if (n + 3 < N && (N & 3) == 0) {
-                h4 v = {(_Float16)acc[i][j][0], (_Float16)acc[i][j][1], (_Float16)acc[i][j][2], (_Float16)acc[i][j][3]};
-                *reinterpret_cast<h4 *>(o) = v;
-            } else {
-#pragma unroll
-                for (int v = 0; v < 4; ++v)
-                    if (n + v < N)
-                        o[v] = (_Float16)acc[i][j][v];
-            }
-        }
-    }
-}
-
 } // namespace
 
 int fq_launch_gemm(const void *x, int M, const fq_packed_ref &w, void *out, fq_stream st)
@@ -283,19 +223,9 @@ int fq_launch_gemm(const void *x, int M, const fq_packed_ref &w, void *out, fq_s
 
 int fq_launch_dense(const void *x, int M, const void *W, int N, int K, void *out, fq_stream st)
 {
-    constexpr int BM = 256, BN = 128;
-    constexpr size_t lds = (size_t)(BM + BN) * 256;
-    auto kern = dgemm_kernel<BM, BN>;
-    static bool configured = false;
-    if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess)
-            return (int)e;
-        configured = true;
-    }
-    dim3 grid((N + BN - 1) / BN, (M + BM - 1) / BM), block(256);
-    hipLaunchKernelGGL(kern, grid, block, lds, st, static_cast<const _Float16 *>(x), M,
-                       static_cast<const _Float16 *>(W), N, K, static_cast<_Float16 *>(out));
+    dim3 grid((N + QBN - 1) / QBN, (M + QBM - 1) / QBM), block(256);
+    hipLaunchKernelGGL(qgemm_kernel<DENSE>, grid, block, 0, st, static_cast<const _Float16 *>(x), M,
+                       static_cast<const uint32_t *>(W), static_cast<const _Float16 *>(nullptr),
+                       static_cast<const _Float16 *>(nullptr), N, K, static_cast<_Float16 *>(out));
     return (int)hipGetLastError();
 }
