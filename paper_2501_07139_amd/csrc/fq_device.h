@@ -14,6 +14,9 @@ typedef float f4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u2v __attribute__((ext_vector_type(2)));
 typedef uint32_t u4v __attribute__((ext_vector_type(4)));
 
+// s_waitcnt immediate that waits for all vector-memory loads only (vmcnt = 0, expcnt and lgkmcnt left at their maxima)
+#define FQ_WAIT_VMCNT0 0x0f70
+
 __device__ __forceinline__ h2 as_h2(uint32_t u) { return __builtin_bit_cast(h2, u); }
 __device__ __forceinline__ uint32_t as_u32(h2 h) { return __builtin_bit_cast(uint32_t, h); }
 

@@ -14,8 +14,8 @@
 // per load), dequantizes them there and feeds the matrix core: weights never
 // touch LDS and are unpacked once per workgroup.  Activations are shared by the
 // four wavefronts through a double-buffered LDS tile, row-major with 16-byte
-// chunks XOR-swizzled by row so that the coalesced global->LDS copy and the
-// operand reads are both free of bank conflicts.  Loads for group g+1 are issued
+// chunks XOR-swizzled by row so that the coalesced copy and the operand reads are
+// both free of bank conflicts; the copy goes from global memory straight into LDS.  Loads for group g+1 are issued
 // before the MFMAs of group g; one barrier per iteration.
 //
 // The unquantized head runs the same kernel: its fp16 weights are read from the row-major matrix
@@ -26,7 +26,7 @@
 namespace {
 
 // ------------------------------------------------------------ quantized GEMM
-constexpr int QBM = 128, QNB = 2, QBN = 64 * QNB, QMB = QBM / 16; // per wave: QNB weight blocks x QMB activation blocks
+constexpr int QBM = 128, QMB = QBM / 16; // per wave: QNB weight blocks (template) x QMB activation blocks
 
 constexpr int DENSE = 16; // BITS value of the unquantized fp16 weight path (the vocabulary head)
 
@@ -59,25 +59,20 @@ __device__ __forceinline__ void load_wchunk(WChunk<BITS> &w, const uint32_t *__r
         return;
     } else {
     constexpr int SUB = Fmt<BITS>::SUB;
-    if (rb16 < Np16) {
-        const uint32_t *tile = packed + ((size_t)(rb16 / SUB) * G + g) * tile_dwords<BITS>();
-        load_chunk<BITS>(tile, rb16 % SUB, lane, w.c);
-        const size_t meta = ((size_t)rb16 * G + g) * 16 + (lane & 15);
-        w.scale = scales[meta];
-        w.zero = zeros[meta];
-    } else {
-#pragma unroll
-        for (int i = 0; i < BITS; ++i)
-            w.c[i] = 0;
-        w.scale = (_Float16)0.f;
-        w.zero = (_Float16)0.f;
-    }
+    // blocks past the end of the matrix re-read the last block: their results are never stored, and
+    // loads without a branch keep the count of loads in flight known to the compiler
+    const int rb = min(rb16, Np16 - 1);
+    const uint32_t *tile = packed + ((size_t)(rb / SUB) * G + g) * tile_dwords<BITS>();
+    load_chunk<BITS>(tile, rb % SUB, lane, w.c);
+    const size_t meta = ((size_t)rb * G + g) * 16 + (lane & 15);
+    w.scale = scales[meta];
+    w.zero = zeros[meta];
     }
 }
 
 // Two workgroups per CU (two wavefronts per SIMD): a single wavefront cannot keep the matrix pipe
 // busy, and two independent workgroups overlap one's unpack/copy phase with the other's MFMAs.
-template <int BITS>
+template <int BITS, int QNB>
 __global__ __launch_bounds__(256, 2) void qgemm_kernel(const _Float16 *__restrict__ x, int M,
                                                        const uint32_t *__restrict__ packed,
                                                        const _Float16 *__restrict__ scales,
@@ -86,16 +81,18 @@ __global__ __launch_bounds__(256, 2) void qgemm_kernel(const _Float16 *__restric
 {
     __shared__ h8 Xs[2][QBM * 16]; // chunk ch of row r at r*16 + (ch ^ (r & 15))
 
+    constexpr int QBN = 64 * QNB;
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
+    const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int m0 = blockIdx.y * QBM, n0 = blockIdx.x * QBN;
     const int G = K >> 7;
     const int Np16 = BITS == DENSE ? N : ((N + 63) / 64 * 64) >> 4; // sixteen-row blocks present (dense: rows)
     const int rb0 = (n0 >> 4) + wave * QNB; // first sixteen-row weight block of this wave
 
-    // activation copy: 8 chunks of 16 bytes per thread per group; row = tid/16 + 16*i, chunk = tid%16
-    const int xrow = tid >> 4, xch = tid & 15;
-    const int xdst = xrow * 16 + (xch ^ (xrow & 15));
+    // activation copy, global memory straight into LDS (no register hop): the i-th load of a wavefront
+    // fills the 64 consecutive 16-byte slots from 64*wave + 256*i, lane by lane; slot (row, pos) holds
+    // chunk pos ^ (row & 15) of its row, so each lane fetches that chunk.  Rows past M re-read row M-1.
+    const int xrow = 4 * wave + (lane >> 4), xch = (lane & 15) ^ (xrow & 15);
     const _Float16 *xsrc[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i)
@@ -108,18 +105,15 @@ __global__ __launch_bounds__(256, 2) void qgemm_kernel(const _Float16 *__restric
         for (int j = 0; j < QMB; ++j)
             acc[i][j] = f4{0.f, 0.f, 0.f, 0.f};
 
-    h8 xr[8];
     WChunk<BITS> wc[QNB];
 #pragma unroll
     for (int i = 0; i < 8; ++i)
-        xr[i] = *reinterpret_cast<const h8 *>(xsrc[i]);
+        __builtin_amdgcn_global_load_lds(xsrc[i], &Xs[0][64 * wave + 256 * i], 16, 0, 0);
 #pragma unroll
     for (int i = 0; i < QNB; ++i)
         load_wchunk<BITS>(wc[i], packed, scales, zeros, rb0 + i, Np16, G, 0, lane);
-#pragma unroll
-    for (int i = 0; i < 8; ++i)
-        Xs[0][xdst + 256 * i] = xr[i];
-    __syncthreads();
+    __builtin_amdgcn_s_waitcnt(FQ_WAIT_VMCNT0); // the copies into LDS have landed ...
+    __syncthreads();                            // ... in every wavefront
 
     for (int g = 0; g < G; ++g) {
         const int cur = g & 1;
@@ -148,7 +142,8 @@ __global__ __launch_bounds__(256, 2) void qgemm_kernel(const _Float16 *__restric
         if (more) {
 #pragma unroll
             for (int i = 0; i < 8; ++i)
-                xr[i] = *reinterpret_cast<const h8 *>(xsrc[i] + (size_t)(g + 1) * 128);
+                __builtin_amdgcn_global_load_lds(xsrc[i] + (size_t)(g + 1) * 128, &Xs[cur ^ 1][64 * wave + 256 * i], 16,
+                                                 0, 0);
 #pragma unroll
             for (int i = 0; i < QNB; ++i)
                 load_wchunk<BITS>(wc[i], packed, scales, zeros, rb0 + i, Np16, G, g + 1, lane);
@@ -168,11 +163,7 @@ __global__ __launch_bounds__(256, 2) void qgemm_kernel(const _Float16 *__restric
                 for (int j = 0; j < QMB; ++j)
                     acc[i][j] = mfma16x16x32(a[i][s], b[j], acc[i][j]);
         }
-        if (more) {
-#pragma unroll
-            for (int i = 0; i < 8; ++i)
-                Xs[cur ^ 1][xdst + 256 * i] = xr[i];
-        }
+        __builtin_amdgcn_s_waitcnt(FQ_WAIT_VMCNT0);
         __syncthreads();
     }
 
@@ -199,14 +190,33 @@ __global__ __launch_bounds__(256, 2) void qgemm_kernel(const _Float16 *__restric
     }
 }
 
+// Weight-tile width.  Wide tiles (each wavefront 128 x 64) halve the LDS reads and activation copies per
+// MFMA but need at least two workgroups per CU to keep both wavefront slots of every SIMD filled.
+int wide_tiles_pay(int M, int N)
+{
+    const long tiles = (long)((N + 255) / 256) * ((M + QBM - 1) / QBM);
+    return tiles >= 2 * 256;
+}
+
+template <int BITS, int QNB>
+int launch_tile(const void *x, int M, const void *packed, const void *scales, const void *zeros, int N, int K,
+                void *out, fq_stream st)
+{
+    constexpr int QBN = 64 * QNB;
+    dim3 grid((N + QBN - 1) / QBN, (M + QBM - 1) / QBM), block(256);
+    hipLaunchKernelGGL((qgemm_kernel<BITS, QNB>), grid, block, 0, st, static_cast<const _Float16 *>(x), M,
+                       static_cast<const uint32_t *>(packed), static_cast<const _Float16 *>(scales),
+                       static_cast<const _Float16 *>(zeros), N, K, static_cast<_Float16 *>(out));
+    return (int)hipGetLastError();
+}
+
 template <int BITS>
 int launch_q(const void *x, int M, const fq_packed_ref &w, void *out, fq_stream st)
 {
-    dim3 grid((w.N + QBN - 1) / QBN, (M + QBM - 1) / QBM), block(256);
-    hipLaunchKernelGGL(qgemm_kernel<BITS>, grid, block, 0, st, static_cast<const _Float16 *>(x), M,
-                       static_cast<const uint32_t *>(w.packed), static_cast<const _Float16 *>(w.scales),
-                       static_cast<const _Float16 *>(w.zeros), w.N, w.K, static_cast<_Float16 *>(out));
-    return (int)hipGetLastError();
+    // 3- and 8-bit operands do not fit the register budget of a wide tile
+    if ((BITS == 2 || BITS == 4) && wide_tiles_pay(M, w.N))
+        return launch_tile<(BITS == 2 || BITS == 4) ? BITS : 4, 4>(x, M, w.packed, w.scales, w.zeros, w.N, w.K, out, st);
+    return launch_tile<BITS, 2>(x, M, w.packed, w.scales, w.zeros, w.N, w.K, out, st);
 }
 
 } // namespace
@@ -223,9 +233,5 @@ int fq_launch_gemm(const void *x, int M, const fq_packed_ref &w, void *out, fq_s
 
 int fq_launch_dense(const void *x, int M, const void *W, int N, int K, void *out, fq_stream st)
 {
-    dim3 grid((N + QBN - 1) / QBN, (M + QBM - 1) / QBM), block(256);
-    hipLaunchKernelGGL(qgemm_kernel<DENSE>, grid, block, 0, st, static_cast<const _Float16 *>(x), M,
-                       static_cast<const uint32_t *>(W), static_cast<const _Float16 *>(nullptr),
-                       static_cast<const _Float16 *>(nullptr), N, K, static_cast<_Float16 *>(out));
-    return (int)hipGetLastError();
+    return launch_tile<DENSE, 2>(x, M, W, nullptr, nullptr, N, K, out, st);
 }
