@@ -84,7 +84,17 @@ __global__ __launch_bounds__(256, 2) void qgemm_kernel(const _Float16 *__restric
     constexpr int QBN = 64 * QNB;
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int m0 = blockIdx.y * QBM, n0 = blockIdx.x * QBN;
+    // Workgroups are dealt to the eight XCDs round-robin and each XCD has its own L2.  Give XCD x the
+    // x-th contiguous run of tiles, and order tiles in bands of four activation row-tiles (row-tile
+    // fastest): the tiles resident on one XCD then form a block of about 4 x 16, so its L2 fetches a few
+    // activation row-tiles and a few weight tiles instead of a whole matrix.
+    const int NT = (N + QBN - 1) / QBN, MT = (M + QBM - 1) / QBM, total = NT * MT;
+    const int per_xcd = (total + 7) >> 3;
+    const int tile = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (tile >= total)
+        return; // uniform over the workgroup, before any barrier
+    const int band = tile / (4 * NT), rest = tile - band * 4 * NT, height = min(4, MT - 4 * band);
+    const int m0 = (4 * band + rest % height) * QBM, n0 = (rest / height) * QBN;
     const int G = K >> 7;
     const int Np16 = BITS == DENSE ? N : ((N + 63) / 64 * 64) >> 4; // sixteen-row blocks present (dense: rows)
     const int rb0 = (n0 >> 4) + wave * QNB; // first sixteen-row weight block of this wave
@@ -203,7 +213,8 @@ int launch_tile(const void *x, int M, const void *packed, const void *scales, co
                 void *out, fq_stream st)
 {
     constexpr int QBN = 64 * QNB;
-    dim3 grid((N + QBN - 1) / QBN, (M + QBM - 1) / QBM), block(256);
+    const int total = ((N + QBN - 1) / QBN) * ((M + QBM - 1) / QBM);
+    dim3 grid(8 * ((total + 7) / 8)), block(256);
     hipLaunchKernelGGL((qgemm_kernel<BITS, QNB>), grid, block, 0, st, static_cast<const _Float16 *>(x), M,
                        static_cast<const uint32_t *>(packed), static_cast<const _Float16 *>(scales),
                        static_cast<const _Float16 *>(zeros), N, K, static_cast<_Float16 *>(out));
