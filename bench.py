@@ -62,6 +62,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
     ap.add_argument("--cpu-rows", type=int, default=16, help="rows of leg A the oracle is timed on")
+    ap.add_argument("--single-launches", action="store_true",
+                    help="for counter runs: a 64 MiB device copy, then one launch of each linear at M=2048 and M=1, no timing")
     return ap.parse_args()
 
 
@@ -133,6 +135,24 @@ def main():
     def step():
         leg_a()
         leg_b()
+
+    if args.single_launches:
+        src = torch.empty(64 << 20, dtype=torch.uint8, device=dev).random_(0, 255)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)  # reference dispatch: reads 64 MiB, writes 64 MiB
+        torch.cuda.synchronize()
+        u = fq.fq_glue(0, x_fwd)
+        mm = torch.empty((M_FWD, FFN), dtype=torch.float16, device=dev).normal_()
+        for j, (N, K) in enumerate(shapes):
+            w = block[j][int(bitvec[j])]
+            fq.fq_qlinear(mm if K == FFN else u, w)
+            torch.cuda.synchronize()
+            fq.fq_qlinear((mm if K == FFN else u)[:1].contiguous(), w)
+            torch.cuda.synchronize()
+        print("single launches done: copy, then (M=2048, M=1) for " + ", ".join(
+            "%s %d-bit" % (fq_synth.MATRIX_NAMES[j], int(bitvec[j])) for j in range(7)))
+        return
 
     # ------------------------------------------------------- algorithmic work
     gemm_flops = sum(2.0 * M_FWD * N * K for N, K in shapes)

@@ -302,3 +302,73 @@ def test_block_steps_teacher_forced(fq, torch):
         w = stack.layers[0][j][int(bitvec[j])]
         y = host16(fq.fq_qlinear(dev(torch, t[inputs[j]]), w))
         assert qerr(y, oracle.qlinear(t[inputs[j]], mats[j])) <= TOL, outputs[j]
+
+
+# ------------------------------------------------- full-size stacks (sampled)
+def build_selected_stack(fq, hidden, ffn, layers, bitvec, seed):
+    """Only the packing the bit vector selects is built for each matrix."""
+    dev_layers, host = [], []
+    for l in range(layers):
+        mats, hmats = [], []
+        for j, (N, K) in enumerate(fq_synth.block_matrix_shapes(hidden, ffn)):
+            b = int(bitvec[7 * l + j])
+            W = fq_synth.weights(seed, N, K, 0.02, l, j)
+            codes, s, z = oracle.quantize_rtn(W, b)
+            mats.append({b: fq.PackedMatrix.from_host(codes, s, z, b)})
+            hmats.append((codes, s, z))
+        dev_layers.append(mats)
+        host.append(hmats)
+    return fq.Stack(dev_layers), host
+
+
+@pytest.mark.parametrize("model,M,probs", [("7b", 2048, (0.3, 0.3, 0.3, 0.1)), ("13b", 4096, (0.6, 0.3, 0.1, 0.0)),
+                                           ("7b", 1, (0.3, 0.3, 0.3, 0.1)), ("13b", 1, (0.6, 0.3, 0.1, 0.0))],
+                         ids=["7b_M2048", "13b_M4096", "7b_M1", "13b_M1"])
+def test_llama_shaped_stack_sampled_rows(fq, torch, model, M, probs):
+    """Two blocks at Llama-2 7B / 13B shapes in the launch configuration the benchmark times; rows of the
+    stack are independent, so the oracle runs a sample of them through both blocks."""
+    sh = fq_synth.MODEL_SHAPES[model]
+    L = 2
+    bitvec = fq_synth.bit_vector(11, 7 * L, probs=probs)
+    stack, host = build_selected_stack(fq, sh["hidden"], sh["ffn"], L, bitvec, 500)
+    x = fq_synth.activations(501, M, sh["hidden"])
+    got = host16(fq.fq_stack_forward(stack, bitvec, dev(torch, x)))
+    assert np.all(np.isfinite(got.astype(np.float32)))
+    rows = np.arange(M) if M == 1 else np.array([0, 1, M // 2 - 1, M // 2, M - 129, M - 1])
+    mats = [[oracle.dequant(*host[l][j]) for j in range(7)] for l in range(L)]
+    want = oracle.stack_forward(x[rows], mats)
+    diff = np.abs(got[rows].astype(np.float64) - want.astype(np.float64))
+    assert diff.max() <= 2e-2 and diff.mean() <= 2e-3
+    # first block teacher-forced at the qlinear tolerance: the GPU's own u against the oracle's linear
+    u = oracle.rms_rows(x[rows].astype(np.float64))
+    w0 = stack.layers[0][0][int(bitvec[0])]
+    y = host16(fq.fq_qlinear(dev(torch, np.ascontiguousarray(u)), w0))
+    assert qerr(y, oracle.qlinear(u, mats[0][0])) <= TOL
+
+
+def test_ensemble_sweep_scores_candidates_like_the_oracle(fq, torch):
+    """Several configuration vectors over one stack, each scored by per-sequence mean NLL through the
+    fp16 head (the candidate loop of Algorithm 1 on a small stand-in model)."""
+    stack, host, sh = build_stack(fq, "tiny", 700)
+    V, T = 1000, 96
+    head = fq_synth.weights(701, V, sh["hidden"], 0.3).astype(np.float16)
+    x = fq_synth.activations(702, T, sh["hidden"])
+    labels = fq_synth.labels(703, T, V)
+    dhead, dx, dl = dev(torch, head), dev(torch, x), dev(torch, labels)
+    scores = []
+    for cand in range(4):
+        bitvec = fq_synth.bit_vector(cand, 7 * sh["layers"], probs=(0.25, 0.25, 0.25, 0.25))
+        h = fq.fq_stack_forward(stack, bitvec, dx)
+        logits = fq.fq_dense_f16(h, dhead)
+        nll = fq.fq_token_nll(logits, dl).cpu().numpy().astype(np.float64)
+        # the loss kernel against the oracle on the very logits it read: the 1e-3 per-sequence bar
+        ref_same_logits = oracle.token_nll(host16(logits), labels)
+        assert abs(nll.mean() - ref_same_logits.mean()) <= 1e-3
+        # whole chain against the oracle's own forward: fp16 re-rounding lets it drift a little
+        mats = [[oracle.dequant(*host[l][j][int(bitvec[7 * l + j])]) for j in range(7)] for l in range(sh["layers"])]
+        hx = oracle.stack_forward(x, mats)
+        ref = oracle.token_nll(oracle.round_f16(oracle.dense_f16(hx, head)), labels)
+        assert abs(nll.mean() - ref.mean()) <= 2e-2
+        scores.append((nll.mean(), ref.mean()))
+    # the ranking the search would use is the oracle's
+    assert np.array_equal(np.argsort([s[0] for s in scores]), np.argsort([s[1] for s in scores]))
