@@ -42,7 +42,7 @@ SEED = 1
 # WRITE_SIZE, KiB per dispatch) scaled by what the same counters read for a 64 MiB device copy (FETCH_SIZE
 # reads 0.500 of the true bytes on this machine, WRITE_SIZE 1.000).  Valid only for the kernel sources whose
 # digest is recorded with it; bench.py reports null once they have changed.
-GEMM_TRAFFIC = {"kernel_digest": "", "fetch_bytes": None, "write_bytes": None}
+GEMM_TRAFFIC = {"kernel_digest": "860f5ae0dbab9890", "fetch_bytes": 889.0e6, "write_bytes": 174.2e6}  # profiles/qgemm_gemv_llama2-7b-block_hbm_traffic.txt
 
 
 def kernel_digest() -> str:
