@@ -164,7 +164,7 @@ extern "C" int fq_stack_forward(const fq_layer *layers, int L, const uint8_t *bi
     bool decode = M <= 16;
     for (int l = 0; l < L && decode; ++l)
         for (int j = 0; j < 7; ++j)
-            decode = decode && fq_gemv_can_stream(M, layers[l].m[j].K, bitvec[7 * l + j]);
+            decode = decode && fq_gemv_can_stream(M, layers[l].m[j].K, bitvec[7 * l + j], j == 3 ? 3 : 2);
 
     const void *xcur = x_in;
     for (int l = 0; l < L; ++l) {

@@ -92,12 +92,13 @@ __device__ __forceinline__ uint32_t code_at(const uint32_t (&C)[BITS], int t)
 // ---------------------------------------------------------------------------
 #define FQ_EXP1024 0x64006400u
 
-// The exponent pattern held in a scalar register: with only the mask as a literal, (w & mask) | exp
-// is a single and-or instruction.
+// The exponent pattern held in a vector register: the three-operand and-or instruction takes no
+// literal and only one scalar operand, so with the mask in a scalar register and the exponent in a
+// vector register (w & mask) | exp is a single instruction.
 __device__ __forceinline__ uint32_t exp1024_reg()
 {
     uint32_t e = FQ_EXP1024;
-    asm volatile("" : "+s"(e));
+    asm volatile("" : "+v"(e));
     return e;
 }
 

@@ -159,16 +159,37 @@ struct GemvInput {
 };
 
 
+// Workgroup barrier that orders LDS accesses only: waits for this wavefront's LDS operations, then for
+// the other wavefronts.  __syncthreads() also fences, and in a kernel that copies into LDS through the
+// vector-memory path the compiler makes that fence wait for every vector load in flight: here that
+// would be the weights.  The memory clobber keeps the compiler from moving accesses across it.
+__device__ __forceinline__ void lds_barrier()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+// Sum over each aligned run of 16 lanes, in all of its lanes: four adds whose second operand comes
+// through the lane-permute path of the ALU (swap within pairs, swap pairs within quads, rotate the row
+// by 4 and by 8).
+__device__ __forceinline__ float row16_sum(float v)
+{
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xB1, 0xF, 0xF, true));
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x4E, 0xF, 0xF, true));
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x124, 0xF, 0xF, true));
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x128, 0xF, 0xF, true));
+    return v;
+}
+
 // Sum over the workgroup, the same value in every thread (two barriers).
 __device__ __forceinline__ float gemv_block_sum(float v, float *part)
 {
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1)
         v += __shfl_xor(v, o, 64);
-    __syncthreads();
+    lds_barrier();
     if ((threadIdx.x & 63) == 0)
         part[threadIdx.x >> 6] = v;
-    __syncthreads();
+    lds_barrier();
     float sum = 0.f;
 #pragma unroll
     for (int w = 0; w < GNW; ++w)
@@ -202,150 +223,214 @@ __device__ __forceinline__ float stage_factor(int s, int e)
 
 // Position in the stream of (supertile row, group) items of one wavefront.
 struct GemvCursor {
-    int j, t; // j-th supertile row of this workgroup, t-th group of this wavefront in it
+    int rb, t; // supertile row, t-th group of this wavefront in it
 };
 
-template <int BITS>
-__device__ __forceinline__ void gemv_body(const GemvJob &job, int bj, const GemvInput &in, int M, int K,
+// Inputs the transform of each mode reads.
+template <int MODE>
+struct GemvInputs { static constexpr int N = MODE == 2 ? 3 : (MODE >= 3 ? 2 : 1); };
+
+// One chunk of the block's tensor that feeds the last rms, in fp32.
+template <int MODE>
+__device__ __forceinline__ void gemv_combine(const h8 (&r)[GemvInputs<MODE>::N], float (&v)[8])
+{
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        float t = (float)r[0][e];
+        if constexpr (MODE == 2)
+            t = t + (float)r[1][e] + (float)r[2][e];
+        else if constexpr (MODE == 3)
+            t = (float)(_Float16)(t + (float)r[1][e]); // the sum is a stored fp16 tensor
+        else if constexpr (MODE == 4)
+            t = t * __builtin_amdgcn_rcpf(1.0f + __expf(-t)) * (float)r[1][e]; // reciprocal good to 1 ulp
+        else if constexpr (MODE == 5)
+            t = t + (float)r[1][e];
+        v[e] = t;
+    }
+}
+
+// s_waitcnt immediate: vector-memory loads in flight <= n (n < 64), the other counters left alone
+constexpr int gemv_wait_vmcnt(int n) { return 0x0f70 | (n & 15) | ((n >> 4) << 14); }
+
+template <int BITS, int MODE>
+__device__ __forceinline__ void gemv_body(const GemvJob job, int bj, const GemvInput in, int M, int K,
                                           unsigned char *smem, float *part)
 {
     constexpr int SUB = Fmt<BITS>::SUB, ROWS = Fmt<BITS>::ROWS, D = GemvDepth<BITS>::D, TILE = tile_dwords<BITS>();
+    constexpr int NIN = GemvInputs<MODE>::N, STEP = 64 * GNW;
+    // vector loads one fill of the ring issues: planes, scales and zeros of every slot (none of them
+    // can merge: they are at least a kilobyte apart or come from different arrays)
+    constexpr int RING_LOADS = D * (Fmt<BITS>::PLANES + 2 * SUB);
+    static_assert(RING_LOADS < 64, "the wait below counts the ring's loads");
     const int G = K >> 7;
     h8 *xl = reinterpret_cast<h8 *>(smem);                             // [K/8][M] staged activations
     float *xsum = reinterpret_cast<float *>(smem + (size_t)M * K * 2); // [G][M] sum of x over the group
     float *csum = xsum + (size_t)G * M;                                // [G][M] 1024 * sum of staged x
     float *red = csum + (size_t)G * M;                                 // [2][GNW][SUB*4][64]
+    h8 *raw = reinterpret_cast<h8 *>(red); // [NIN][trips][STEP] raw input row; free again before the first reduction
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6); // scalar: keeps tile addressing in SGPRs
     const int m = lane & 15, c = lane >> 4;
     const int NRB = ((job.N + 63) / 64 * 64) / ROWS;
-    const int T = (G + GNW - 1) / GNW;                                 // groups per wavefront and supertile row
-    const int J = bj < NRB ? (NRB - bj + job.nblk - 1) / job.nblk : 0; // supertile rows of this workgroup
-    const int I = J * T;
+    const int T = (G + GNW - 1) / GNW; // groups per wavefront and supertile row
+    const int nblk = job.nblk;
+    const uint32_t *const packed = job.packed;
+    const _Float16 *const scales = job.scales, *const zeros = job.zeros;
 
-    if (J == 0)
+    if (bj >= NRB)
         return; // uniform: nothing to do for this workgroup
 
-    // Loads are unconditional (indices clamped into the matrix) so that the number of loads in flight is
-    // known at compile time and a wavefront only ever waits for the oldest slot of its ring.
+    // ---- the input row first, copied from global memory straight into LDS (no registers): the
+    // staging below then waits for these copies only, not for the weights issued behind them.  The
+    // i-th copy of a wavefront fills 64 consecutive 16-byte slots, lane by lane; chunk indices past the
+    // end of the row are clamped (their slots are never read).
+    const int chunks = K >> 3, trips = (chunks + STEP - 1) / STEP;
+    const _Float16 *const src[3] = {in.a, in.b, in.c};
+    for (int t = 0; t < trips; ++t) {
+        const size_t off = (size_t)min(tid + STEP * t, chunks - 1) * 8;
+#pragma unroll
+        for (int i = 0; i < NIN; ++i)
+            __builtin_amdgcn_global_load_lds(src[i] + off, &raw[(i * trips + t) * STEP + 64 * wave], 16, 0, 0);
+    }
+    __builtin_amdgcn_sched_barrier(0); // the weights' loads stay behind the copies
+
+    // ---- weights: unconditional loads (indices clamped into the matrix) so that a wavefront only
+    // ever waits for the oldest slot of its ring.
     GemvSlot<BITS> ring[D];
-    GemvCursor pre = {0, 0};
+    GemvCursor pre = {bj, 0};
+    // addresses are a uniform base plus a 32-bit lane offset: they stay in scalar registers
+    const uint32_t plane_off = (uint32_t)lane * 4u, meta_off = (uint32_t)c * 4u;
     auto issue = [&](GemvSlot<BITS> &sl) {
         const int g = min(wave + GNW * pre.t, G - 1);
-        const int rb = bj + min(pre.j, J - 1) * job.nblk;
-        const uint32_t *tile = job.packed + ((size_t)rb * G + g) * TILE;
+        const int rb = pre.rb < NRB ? pre.rb : bj; // past the end: any row of ours, the data is not used
+        const uint32_t *tile = packed + ((size_t)rb * G + g) * TILE;
 #pragma unroll
         for (int p = 0; p < Fmt<BITS>::PLANES; ++p)
-            sl.plane[p] = *reinterpret_cast<const u4v *>(tile + p * 256 + lane * 4);
+            sl.plane[p] = *reinterpret_cast<const u4v *>(tile + p * 256 + plane_off);
 #pragma unroll
         for (int u = 0; u < SUB; ++u) {
-            const size_t meta = ((size_t)(rb * SUB + u) * G + g) * 16 + 4 * c;
-            sl.scale[u] = *reinterpret_cast<const h4 *>(job.scales + meta);
-            sl.zero[u] = *reinterpret_cast<const h4 *>(job.zeros + meta);
+            const size_t meta = ((size_t)(rb * SUB + u) * G + g) * 16;
+            sl.scale[u] = *reinterpret_cast<const h4 *>(scales + meta + meta_off);
+            sl.zero[u] = *reinterpret_cast<const h4 *>(zeros + meta + meta_off);
         }
         if (++pre.t == T) {
             pre.t = 0;
-            ++pre.j;
+            pre.rb += nblk;
         }
     };
-    // weights first: they do not depend on the staging below
 #pragma unroll
-    for (int d = 0; d < D; ++d)
+    for (int d = 0; d < D; ++d) {
         issue(ring[d]);
+        __builtin_amdgcn_sched_barrier(0); // slot by slot, the order in which the loop below waits for them
+    }
 
-    // stage x, one activation row at a time: the input transform of the block (see GemvInput) runs here,
-    // in every workgroup alike, so that the row-wise glue between two linears costs no launch of its own.
-    // The inputs are re-read (from L2) in each pass instead of being held in registers.
-    // Chunk kc of row mm (8 halves at k = 8*kc) goes to xl[kc*M + mm], divided by 2^p.
-    const int chunks = K >> 3;
-    for (int mm = 0; mm < M; ++mm) {
-        const size_t row = (size_t)mm * K;
-        auto base = [&](int kc, float (&v)[8]) {
-            const h8 va = *reinterpret_cast<const h8 *>(in.a + row + kc * 8);
-            h8 vb = va, vc = va;
-            if (in.mode >= 2)
-                vb = *reinterpret_cast<const h8 *>(in.b + row + kc * 8);
-            if (in.mode == 2)
-                vc = *reinterpret_cast<const h8 *>(in.c + row + kc * 8);
+    // ---- stage x, one activation row at a time: the input transform of the block (see GemvInput) runs
+    // here, in every workgroup alike, so that the row-wise glue between two linears costs no launch of
+    // its own.  Chunk kc of row mm (8 halves at k = 8*kc) goes to xl[kc*M + mm], divided by 2^p.
+    // MODE 4 (the expensive transform) is evaluated once: the first pass over the row leaves the eight
+    // fp32 products in the two 16-byte slots of its inputs, which only this thread touches.
+    auto fetch = [&](int t, float (&v)[8], bool first) { // this thread's chunk of trip t, combined
+        h8 r[NIN];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                float t = (float)va[e];
-                if (in.mode == 2)
-                    t = t + (float)vb[e] + (float)vc[e];
-                else if (in.mode == 3)
-                    t = (float)(_Float16)(t + (float)vb[e]); // the sum is a stored fp16 tensor
-                else if (in.mode == 4)
-                    t = t / (1.0f + __expf(-t)) * (float)vb[e];
-                else if (in.mode == 5)
-                    t = t + (float)vb[e];
-                v[e] = t;
+        for (int i = 0; i < NIN; ++i)
+            r[i] = raw[(i * trips + t) * STEP + tid];
+        if constexpr (MODE == 4) {
+            if (first) {
+                gemv_combine<MODE>(r, v);
+                raw[t * STEP + tid] = __builtin_bit_cast(h8, f4{v[0], v[1], v[2], v[3]});
+                raw[(trips + t) * STEP + tid] = __builtin_bit_cast(h8, f4{v[4], v[5], v[6], v[7]});
+            } else {
+                const f4 lo = __builtin_bit_cast(f4, r[0]), hi = __builtin_bit_cast(f4, r[1]);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    v[e] = lo[e];
+                    v[4 + e] = hi[e];
+                }
             }
-        };
-        float inv1 = 1.0f, inv2 = 1.0f;
-        if (in.mode != 0) {
-            float ss = 0.f;
-            for (int kc = tid; kc < chunks; kc += 64 * GNW) {
+        } else {
+            gemv_combine<MODE>(r, v);
+        }
+    };
+    // sum of squares of this thread's part of the row; second: of the fp16 result of the first rms
+    auto squares = [&](bool second, float inv1) {
+        float ss = 0.f;
+        for (int t = 0; t < trips; ++t)
+            if (tid + STEP * t < chunks) {
                 float v[8];
-                base(kc, v);
+                fetch(t, v, !second);
 #pragma unroll
-                for (int e = 0; e < 8; ++e)
-                    ss += v[e] * v[e];
+                for (int e = 0; e < 8; ++e) {
+                    const float y = second ? (float)(_Float16)(v[e] * inv1) : v[e];
+                    ss += y * y;
+                }
             }
-            inv1 = 1.0f / sqrtf(gemv_block_sum(ss, part) / (float)K + 1e-5f);
-            if (in.mode == 5) { // rms twice: the first result is the stored fp16 block output
-                ss = 0.f;
-                for (int kc = tid; kc < chunks; kc += 64 * GNW) {
-                    float v[8];
-                    base(kc, v);
+        return ss;
+    };
+    auto stage_row = [&](int mm) {
+        float inv1 = 1.0f, inv2 = 1.0f;
+        if constexpr (MODE != 0) {
+            inv1 = 1.0f / sqrtf(gemv_block_sum(squares(false, 1.0f), part) / (float)K + 1e-5f);
+            if constexpr (MODE == 5) // rms twice: the first result is the stored fp16 block output
+                inv2 = 1.0f / sqrtf(gemv_block_sum(squares(true, inv1), part) / (float)K + 1e-5f);
+        }
+        for (int t = 0; t < trips; ++t) {
+            const int kc = tid + STEP * t;
+            if (kc < chunks) { // the 16 lanes that share a group agree: chunks is a multiple of 16
+                float v[8];
+                fetch(t, v, false);
+                if constexpr (MODE == 5) {
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        const float y = (float)(_Float16)(v[e] * inv1);
-                        ss += y * y;
+                    for (int e = 0; e < 8; ++e)
+                        v[e] = (float)(_Float16)(v[e] * inv1);
+                }
+                if constexpr (MODE == 3 || MODE == 5) {
+                    if (blockIdx.x == 0) {
+                        h8 o;
+#pragma unroll
+                        for (int e = 0; e < 8; ++e)
+                            o[e] = (_Float16)v[e]; // exact: already fp16 values
+                        *reinterpret_cast<h8 *>(in.aux + (size_t)mm * K + (size_t)kc * 8) = o;
                     }
                 }
-                inv2 = 1.0f / sqrtf(gemv_block_sum(ss, part) / (float)K + 1e-5f);
+                const float inv = MODE == 5 ? inv2 : inv1;
+                const int s = (kc >> 2) & 3;
+                h8 w;
+                float sx = 0.f, sc = 0.f;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const float xe = MODE == 0 ? v[e] : (float)(_Float16)(v[e] * inv);
+                    w[e] = (_Float16)(xe * stage_factor<BITS>(s, e));
+                    sx += xe;
+                    sc += (float)w[e];
+                }
+                xl[(size_t)kc * M + mm] = w;
+                sx = row16_sum(sx);
+                sc = row16_sum(sc);
+                if ((kc & 15) == 0) {
+                    xsum[(kc >> 4) * M + mm] = sx;
+                    csum[(kc >> 4) * M + mm] = 1024.0f * sc;
+                }
             }
         }
-        for (int kc = tid; kc < chunks; kc += 64 * GNW) { // all 16 lanes of a group take the same trips
-            float v[8];
-            base(kc, v);
-            if (in.mode == 5) {
+    };
+    // Row 0 apart from the others: its copies were issued before the weights, so waiting for them leaves
+    // the weights in flight; later rows are fetched behind the weights and wait for everything.
+    __builtin_amdgcn_s_waitcnt(gemv_wait_vmcnt(RING_LOADS)); // the copies of row 0 have landed ...
+    lds_barrier();                                           // ... in every wavefront
+    stage_row(0);
+    for (int mm = 1; mm < M; ++mm) {
+        lds_barrier(); // every thread is done with the previous row
+        for (int t = 0; t < trips; ++t) { // through registers: behind the weights whichever way
+            const size_t off = (size_t)mm * K + (size_t)min(tid + STEP * t, chunks - 1) * 8;
 #pragma unroll
-                for (int e = 0; e < 8; ++e)
-                    v[e] = (float)(_Float16)(v[e] * inv1);
-            }
-            if ((in.mode == 3 || in.mode == 5) && blockIdx.x == 0) {
-                h8 o;
-#pragma unroll
-                for (int e = 0; e < 8; ++e)
-                    o[e] = (_Float16)v[e]; // exact: already fp16 values
-                *reinterpret_cast<h8 *>(in.aux + row + kc * 8) = o;
-            }
-            const float inv = in.mode == 5 ? inv2 : inv1;
-            const int s = (kc >> 2) & 3;
-            h8 w;
-            float sx = 0.f, sc = 0.f;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const float xe = in.mode == 0 ? v[e] : (float)(_Float16)(v[e] * inv);
-                w[e] = (_Float16)(xe * stage_factor<BITS>(s, e));
-                sx += xe;
-                sc += (float)w[e];
-            }
-            xl[(size_t)kc * M + mm] = w;
-#pragma unroll
-            for (int o = 8; o > 0; o >>= 1) {
-                sx += __shfl_xor(sx, o, 64);
-                sc += __shfl_xor(sc, o, 64);
-            }
-            if ((kc & 15) == 0) {
-                xsum[(kc >> 4) * M + mm] = sx;
-                csum[(kc >> 4) * M + mm] = 1024.0f * sc;
-            }
+            for (int i = 0; i < NIN; ++i)
+                raw[(i * trips + t) * STEP + tid] = *reinterpret_cast<const h8 *>(src[i] + off);
         }
+        lds_barrier();
+        stage_row(mm);
     }
-    __syncthreads();
+    lds_barrier(); // x is staged; the raw row (which shares LDS with the reduction buffers) is dead
 
     f4 acc[SUB];
 #pragma unroll
@@ -354,20 +439,26 @@ __device__ __forceinline__ void gemv_body(const GemvJob &job, int bj, const Gemv
 
     const bool live = m < M;
     const int mc = min(m, M - 1), xlane = c * M + mc;
-    GemvCursor cur = {0, 0};
-    for (int i0 = 0; i0 < I; i0 += D) {
+    GemvCursor cur = {bj, 0};
+    int parity = 0;
+    while (cur.rb < NRB) {
 #pragma unroll
         for (int d = 0; d < D; ++d) {
+            // No branch around the item: past the end of a row (or of the matrix) the slot holds a clamped
+            // reload, the item runs on it and its contribution is multiplied by zero.  With a branch, the
+            // compiler could not tell how many loads are in flight and waited for all of them.
             const int g = wave + GNW * cur.t;
-            const bool valid = (i0 + d < I) && (g < G); // past the end the slot holds a clamped reload: skipped
-            if (valid) {
+            const bool valid = (cur.rb < NRB) && (g < G);
+            const int gc = min(g, G - 1);
+            {
                 // lanes of the unused MFMA columns (m >= M) repeat column M-1; their results are never stored
-                const h8 *xg_ptr = xl + (size_t)g * 16 * M + xlane;
+                const h8 *xg_ptr = xl + (size_t)gc * 16 * M + xlane;
                 h8 bx[4];
 #pragma unroll
                 for (int s = 0; s < 4; ++s)
                     bx[s] = xg_ptr[s * 4 * M];
-                const float xg = xsum[g * M + mc], ncg = -csum[g * M + mc];
+                const float xg = xsum[gc * M + mc], ncg = -csum[gc * M + mc];
+                const float keep = valid ? 1.0f : 0.0f;
                 uint32_t dw[4 * Fmt<BITS>::PLANES];
 #pragma unroll
                 for (int p = 0; p < Fmt<BITS>::PLANES; ++p) {
@@ -388,14 +479,14 @@ __device__ __forceinline__ void gemv_body(const GemvJob &job, int bj, const Gemv
 #pragma unroll
                     for (int v = 0; v < 4; ++v) {
                         const float t = fmaf(-(float)ring[d].zero[u][v], xg, p[v]);
-                        acc[u][v] = fmaf((float)ring[d].scale[u][v], t, acc[u][v]);
+                        acc[u][v] = fmaf((float)ring[d].scale[u][v] * keep, t, acc[u][v]);
                     }
                 }
             }
             issue(ring[d]); // the item D places ahead reuses this slot
-            if (i0 + d < I && ++cur.t == T) {
+            if (cur.rb < NRB && ++cur.t == T) {
                 // end of a supertile row: fixed-order reduction over the wavefronts, double-buffered
-                float *rbuf = red + (size_t)(cur.j & 1) * GNW * SUB * 4 * 64;
+                float *rbuf = red + (size_t)parity * GNW * SUB * 4 * 64;
 #pragma unroll
                 for (int u = 0; u < SUB; ++u)
 #pragma unroll
@@ -403,59 +494,75 @@ __device__ __forceinline__ void gemv_body(const GemvJob &job, int bj, const Gemv
                         rbuf[(wave * SUB * 4 + u * 4 + v) * 64 + lane] = acc[u][v];
                         acc[u][v] = 0.f;
                     }
-                __syncthreads();
-                const int rb = bj + cur.j * job.nblk;
+                lds_barrier();
                 if (live) {
                     for (int e = wave; e < SUB * 4; e += GNW) {
                         float sum = 0.f;
 #pragma unroll
                         for (int w = 0; w < GNW; ++w)
                             sum += rbuf[(w * SUB * 4 + e) * 64 + lane];
-                        const int n = rb * ROWS + 16 * (e >> 2) + 4 * c + (e & 3);
+                        const int n = cur.rb * ROWS + 16 * (e >> 2) + 4 * c + (e & 3);
                         if (n < job.N)
                             job.out[(size_t)m * job.N + n] = (_Float16)sum;
                     }
                 }
                 cur.t = 0;
-                ++cur.j;
+                cur.rb += nblk;
+                parity ^= 1;
             }
         }
     }
 }
 
-__global__ __launch_bounds__(64 * GNW, 2) void gemv_stream_kernel(GemvInput in, int M, int K, GemvJobs jobs)
+// Four wavefronts per SIMD, i.e. two workgroups per CU.
+template <int MODE>
+__global__ __launch_bounds__(64 * GNW, 4) void gemv_stream_kernel(GemvInput in, int M, int K, GemvJobs jobs)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     __shared__ float part[GNW];
-    int ji = 0;
-#pragma unroll
-    for (int i = 1; i < 3; ++i)
-        if (i < jobs.count && (int)blockIdx.x >= jobs.j[i].blk0)
-            ji = i;
-    const GemvJob &job = jobs.j[ji];
+    // the job of this workgroup, selected by value so that its fields stay in scalar registers
+    GemvJob job = jobs.j[0];
+    if (jobs.count > 1 && (int)blockIdx.x >= jobs.j[1].blk0)
+        job = jobs.j[1];
+    if (jobs.count > 2 && (int)blockIdx.x >= jobs.j[2].blk0)
+        job = jobs.j[2];
     const int bj = blockIdx.x - job.blk0;
     switch (job.bits) { // uniform across the workgroup
-    case 2: gemv_body<2>(job, bj, in, M, K, smem, part); break;
-    case 3: gemv_body<3>(job, bj, in, M, K, smem, part); break;
-    case 4: gemv_body<4>(job, bj, in, M, K, smem, part); break;
-    default: gemv_body<8>(job, bj, in, M, K, smem, part); break;
+    case 2: gemv_body<2, MODE>(job, bj, in, M, K, smem, part); break;
+    case 3: gemv_body<3, MODE>(job, bj, in, M, K, smem, part); break;
+    case 4: gemv_body<4, MODE>(job, bj, in, M, K, smem, part); break;
+    default: gemv_body<8, MODE>(job, bj, in, M, K, smem, part); break;
     }
+}
+
+typedef void (*GemvKernel)(GemvInput, int, int, GemvJobs);
+
+GemvKernel gemv_kernel_for(int mode)
+{
+    static const GemvKernel table[6] = {gemv_stream_kernel<0>, gemv_stream_kernel<1>, gemv_stream_kernel<2>,
+                                        gemv_stream_kernel<3>, gemv_stream_kernel<4>, gemv_stream_kernel<5>};
+    return table[mode];
 }
 
 constexpr size_t GEMV_MAX_LDS = 152 * 1024;
 
-size_t gemv_stream_lds(int M, int K, int bits)
+// Dynamic LDS of a streaming launch: staged x, the group sums, and one region shared by the raw input
+// row (inputs of the mode, whole trips of 512 chunks) and the reduction buffers.
+size_t gemv_stream_lds(int M, int K, int bits, int inputs)
 {
     const int sub = bits == 3 ? 4 : (bits == 2 ? 2 : 1);
-    return (size_t)M * K * 2 + 2 * (size_t)(K >> 7) * M * 4 + 2 * (size_t)GNW * sub * 4 * 64 * 4;
+    const size_t red = 2 * (size_t)GNW * sub * 4 * 64 * 4;
+    const size_t raw = (size_t)inputs * (((K >> 3) + 64 * GNW - 1) / (64 * GNW)) * (64 * GNW) * 16;
+    return (size_t)M * K * 2 + 2 * (size_t)(K >> 7) * M * 4 + (red > raw ? red : raw);
 }
 
 int rows_per_supertile(int bits) { return bits == 2 ? 32 : (bits == 3 ? 64 : 16); }
 
-// Resident workgroups of the streaming kernel on the device.
-int gemv_resident_blocks(size_t lds, int *out)
+// Resident workgroups of a streaming kernel on the device for a request of dynamic LDS.
+int gemv_resident_blocks(GemvKernel kernel, int slot, size_t lds, int *out)
 {
     static int cus = 0;
+    static bool prepared[6];
     if (cus == 0) {
         int dev = 0, n = 0;
         hipError_t e = hipGetDevice(&dev);
@@ -464,50 +571,56 @@ int gemv_resident_blocks(size_t lds, int *out)
         e = hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev);
         if (e != hipSuccess)
             return (int)e;
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(gemv_stream_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)GEMV_MAX_LDS);
-        if (e != hipSuccess)
-            return (int)e;
         cus = n;
     }
-    // the answer depends only on the LDS request: remember the last few
-    static size_t seen_lds[8];
-    static int seen_blocks[8], seen = 0;
-    for (int i = 0; i < seen; ++i)
-        if (seen_lds[i] == lds) {
-            *out = seen_blocks[i];
+    if (!prepared[slot]) {
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)GEMV_MAX_LDS);
+        if (e != hipSuccess)
+            return (int)e;
+        prepared[slot] = true;
+    }
+    // the answer depends only on the kernel and the LDS request: remember the last few
+    static size_t seen_lds[6][4];
+    static int seen_blocks[6][4], seen[6];
+    for (int i = 0; i < seen[slot]; ++i)
+        if (seen_lds[slot][i] == lds) {
+            *out = seen_blocks[slot][i];
             return 0;
         }
     int per_cu = 0;
-    hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gemv_stream_kernel, 64 * GNW, lds);
+    const hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, 64 * GNW, lds);
     if (e != hipSuccess)
         return (int)e;
     *out = cus * (per_cu > 0 ? per_cu : 1);
-    if (seen < 8) {
-        seen_lds[seen] = lds;
-        seen_blocks[seen++] = *out;
+    if (seen[slot] < 4) {
+        seen_lds[slot][seen[slot]] = lds;
+        seen_blocks[slot][seen[slot]++] = *out;
     }
     return 0;
 }
 
 } // namespace
 
-bool fq_gemv_can_stream(int M, int K, int bits)
+bool fq_gemv_can_stream(int M, int K, int bits, int inputs)
 {
-    return gemv_stream_lds(M, K, bits) <= GEMV_MAX_LDS;
+    return gemv_stream_lds(M, K, bits, inputs) <= GEMV_MAX_LDS;
 }
 
 // Up to three matrices that share the input (same K): one launch.
 int fq_launch_gemv_multi(const fq_gemv_input &src, int M, const fq_packed_ref *w, void *const *outs, int count,
                          fq_stream st)
 {
+    if (src.mode < 0 || src.mode > 5)
+        return (int)hipErrorInvalidValue;
+    const int inputs = src.mode == 2 ? 3 : (src.mode >= 3 ? 2 : 1);
     GemvJobs jobs;
     jobs.count = count;
     size_t lds = 0;
     double bytes[3], total = 0;
     int nrb[3], sum_nrb = 0;
     for (int i = 0; i < count; ++i) {
-        const size_t need = gemv_stream_lds(M, w[i].K, w[i].bits);
+        const size_t need = gemv_stream_lds(M, w[i].K, w[i].bits, inputs);
         lds = lds > need ? lds : need;
         nrb[i] = ((w[i].N + 63) / 64 * 64) / rows_per_supertile(w[i].bits);
         sum_nrb += nrb[i];
@@ -515,7 +628,8 @@ int fq_launch_gemv_multi(const fq_gemv_input &src, int M, const fq_packed_ref *w
         total += bytes[i];
     }
     int resident = 0;
-    if (int e = gemv_resident_blocks(lds, &resident))
+    const GemvKernel kernel = gemv_kernel_for(src.mode);
+    if (int e = gemv_resident_blocks(kernel, src.mode, lds, &resident))
         return e;
     int grid = sum_nrb < resident ? sum_nrb : resident;
     if (grid < count)
@@ -541,13 +655,13 @@ int fq_launch_gemv_multi(const fq_gemv_input &src, int M, const fq_packed_ref *w
         jobs.j[i] = GemvJob{nullptr, nullptr, nullptr, nullptr, 0, 0, blk0, 0};
     const GemvInput in = {static_cast<const _Float16 *>(src.a), static_cast<const _Float16 *>(src.b),
                           static_cast<const _Float16 *>(src.c), static_cast<_Float16 *>(src.aux), src.mode};
-    hipLaunchKernelGGL(gemv_stream_kernel, dim3(blk0), dim3(64 * GNW), lds, st, in, M, w[0].K, jobs);
+    hipLaunchKernelGGL(kernel, dim3(blk0), dim3(64 * GNW), lds, st, in, M, w[0].K, jobs);
     return (int)hipGetLastError();
 }
 
 int fq_launch_gemv(const void *x, int M, const fq_packed_ref &w, void *out, fq_stream st)
 {
-    if (fq_gemv_can_stream(M, w.K, w.bits)) {
+    if (fq_gemv_can_stream(M, w.K, w.bits, 1)) {
         const fq_gemv_input src = {x, nullptr, nullptr, nullptr, 0};
         return fq_launch_gemv_multi(src, M, &w, &out, 1, st);
     }
