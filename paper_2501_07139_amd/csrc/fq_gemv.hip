@@ -126,7 +126,10 @@ int launch_generic(const void *x, int M, const fq_packed_ref &w, void *out, fq_s
 }
 
 // ---------------------------------------------------------------- streaming
-constexpr int GNW = 8; // wavefronts per workgroup
+#ifndef FQ_GNW
+#define FQ_GNW 8
+#endif
+constexpr int GNW = FQ_GNW; // wavefronts per workgroup
 
 // Groups in flight per wavefront.  HBM throughput here follows the bytes in flight (about 3 us of loaded
 // latency): 16 wavefronts per CU times 4-6 KiB each.
@@ -180,27 +183,28 @@ __device__ __forceinline__ float row16_sum(float v)
     return v;
 }
 
-// Sum over the workgroup, the same value in every thread (two barriers).
-__device__ __forceinline__ float gemv_block_sum(float v, float *part)
+// Sum over the workgroup, the same value in every thread.  part holds two sets of per-wavefront
+// partials used in turn (which = 0, 1, 0, ...), so one barrier per sum is enough: a wavefront can only
+// be two sums ahead of another after passing the barrier of the sum in between.
+__device__ __forceinline__ float gemv_block_sum(float v, float *part, int which)
 {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1)
-        v += __shfl_xor(v, o, 64);
-    lds_barrier();
+    v = row16_sum(v);
+    v += __shfl_xor(v, 16, 64);
+    v += __shfl_xor(v, 32, 64);
     if ((threadIdx.x & 63) == 0)
-        part[threadIdx.x >> 6] = v;
+        part[which * GNW + (threadIdx.x >> 6)] = v;
     lds_barrier();
     float sum = 0.f;
 #pragma unroll
     for (int w = 0; w < GNW; ++w)
-        sum += part[w];
+        sum += part[which * GNW + w];
     return sum;
 }
 
 template <int BITS>
 struct GemvSlot {
     u4v plane[Fmt<BITS>::PLANES];
-    h4 scale[Fmt<BITS>::SUB], zero[Fmt<BITS>::SUB];
+    _Float16 scale[Fmt<BITS>::SUB], zero[Fmt<BITS>::SUB]; // of weight row lane % 16 of each sub-block
 };
 
 // 2^-pair_shift for element e of k-step s: the factor applied to x while staging.
@@ -252,7 +256,8 @@ __device__ __forceinline__ void gemv_combine(const h8 (&r)[GemvInputs<MODE>::N],
 // s_waitcnt immediate: vector-memory loads in flight <= n (n < 64), the other counters left alone
 constexpr int gemv_wait_vmcnt(int n) { return 0x0f70 | (n & 15) | ((n >> 4) << 14); }
 
-template <int BITS, int MODE>
+// MV: activation rows a lane finishes per sub-block (1 when M == 1, else 4).
+template <int BITS, int MODE, int MV>
 __device__ __forceinline__ void gemv_body(const GemvJob job, int bj, const GemvInput in, int M, int K,
                                           unsigned char *smem, float *part)
 {
@@ -263,17 +268,17 @@ __device__ __forceinline__ void gemv_body(const GemvJob job, int bj, const GemvI
     constexpr int RING_LOADS = D * (Fmt<BITS>::PLANES + 2 * SUB);
     static_assert(RING_LOADS < 64, "the wait below counts the ring's loads");
     const int G = K >> 7;
-    h8 *xl = reinterpret_cast<h8 *>(smem);                             // [K/8][M] staged activations
-    float *xsum = reinterpret_cast<float *>(smem + (size_t)M * K * 2); // [G][M] sum of x over the group
-    float *csum = xsum + (size_t)G * M;                                // [G][M] 1024 * sum of staged x
-    float *red = csum + (size_t)G * M;                                 // [2][GNW][SUB*4][64]
+    const int T = (G + GNW - 1) / GNW; // groups per wavefront and supertile row
+    const int GP = T * GNW;            // groups rounded up to whole turns of the wavefronts: the rest is zero
+    h8 *xl = reinterpret_cast<h8 *>(smem);                                   // [GP*16][M] staged activations
+    float *xsum = reinterpret_cast<float *>(smem + (size_t)GP * 16 * M * 16); // [GP][16] sum of x over the group
+    float *csum = xsum + (size_t)GP * 16;                                    // [GP][16] 1024 * sum of staged x
+    float *red = csum + (size_t)GP * 16;                                     // [2][GNW][SUB*MV][64]
     h8 *raw = reinterpret_cast<h8 *>(red); // [NIN][trips][STEP] raw input row; free again before the first reduction
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6); // scalar: keeps tile addressing in SGPRs
-    const int m = lane & 15, c = lane >> 4;
     const int NRB = ((job.N + 63) / 64 * 64) / ROWS;
-    const int T = (G + GNW - 1) / GNW; // groups per wavefront and supertile row
     const int nblk = job.nblk;
     const uint32_t *const packed = job.packed;
     const _Float16 *const scales = job.scales, *const zeros = job.zeros;
@@ -299,24 +304,31 @@ __device__ __forceinline__ void gemv_body(const GemvJob job, int bj, const GemvI
     // ever waits for the oldest slot of its ring.
     GemvSlot<BITS> ring[D];
     GemvCursor pre = {bj, 0};
-    // addresses are a uniform base plus a 32-bit lane offset: they stay in scalar registers
-    const uint32_t plane_off = (uint32_t)lane * 4u, meta_off = (uint32_t)c * 4u;
+    // Addresses: a per-row base, recomputed when the stream moves to the next supertile row, plus a
+    // 32-bit offset for the group, plus the lane's own offset.
+    const uint32_t plane_off = (uint32_t)lane * 4u, meta_off = (uint32_t)(lane & 15);
+    const size_t row_tiles = (size_t)G * TILE, row_meta = (size_t)G * 16 * SUB; // per supertile row
+    const uint32_t *tile_row = packed + (size_t)bj * row_tiles;
+    const _Float16 *scale_row = scales + (size_t)bj * row_meta, *zero_row = zeros + (size_t)bj * row_meta;
     auto issue = [&](GemvSlot<BITS> &sl) {
-        const int g = min(wave + GNW * pre.t, G - 1);
-        const int rb = pre.rb < NRB ? pre.rb : bj; // past the end: any row of ours, the data is not used
-        const uint32_t *tile = packed + ((size_t)rb * G + g) * TILE;
+        const uint32_t g = (uint32_t)min(wave + GNW * pre.t, G - 1);
+        const uint32_t *tile = tile_row + g * (uint32_t)TILE;
 #pragma unroll
         for (int p = 0; p < Fmt<BITS>::PLANES; ++p)
             sl.plane[p] = *reinterpret_cast<const u4v *>(tile + p * 256 + plane_off);
 #pragma unroll
         for (int u = 0; u < SUB; ++u) {
-            const size_t meta = ((size_t)(rb * SUB + u) * G + g) * 16;
-            sl.scale[u] = *reinterpret_cast<const h4 *>(scales + meta + meta_off);
-            sl.zero[u] = *reinterpret_cast<const h4 *>(zeros + meta + meta_off);
+            const uint32_t meta = ((uint32_t)u * (uint32_t)G + g) * 16u;
+            sl.scale[u] = scale_row[meta + meta_off];
+            sl.zero[u] = zero_row[meta + meta_off];
         }
         if (++pre.t == T) {
             pre.t = 0;
             pre.rb += nblk;
+            const int rb = pre.rb < NRB ? pre.rb : bj; // past the end: any row of ours, the data is not used
+            tile_row = packed + (size_t)rb * row_tiles;
+            scale_row = scales + (size_t)rb * row_meta;
+            zero_row = zeros + (size_t)rb * row_meta;
         }
     };
 #pragma unroll
@@ -338,8 +350,10 @@ __device__ __forceinline__ void gemv_body(const GemvJob job, int bj, const GemvI
         if constexpr (MODE == 4) {
             if (first) {
                 gemv_combine<MODE>(r, v);
-                raw[t * STEP + tid] = __builtin_bit_cast(h8, f4{v[0], v[1], v[2], v[3]});
-                raw[(trips + t) * STEP + tid] = __builtin_bit_cast(h8, f4{v[4], v[5], v[6], v[7]});
+                if (t > 0) { // trip 0 stays in registers
+                    raw[t * STEP + tid] = __builtin_bit_cast(h8, f4{v[0], v[1], v[2], v[3]});
+                    raw[(trips + t) * STEP + tid] = __builtin_bit_cast(h8, f4{v[4], v[5], v[6], v[7]});
+                }
             } else {
                 const f4 lo = __builtin_bit_cast(f4, r[0]), hi = __builtin_bit_cast(f4, r[1]);
 #pragma unroll
@@ -352,72 +366,98 @@ __device__ __forceinline__ void gemv_body(const GemvJob job, int bj, const GemvI
             gemv_combine<MODE>(r, v);
         }
     };
-    // sum of squares of this thread's part of the row; second: of the fp16 result of the first rms
-    auto squares = [&](bool second, float inv1) {
-        float ss = 0.f;
-        for (int t = 0; t < trips; ++t)
-            if (tid + STEP * t < chunks) {
-                float v[8];
-                fetch(t, v, !second);
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const float y = second ? (float)(_Float16)(v[e] * inv1) : v[e];
-                    ss += y * y;
-                }
-            }
-        return ss;
-    };
+    // The chunk of trip 0 stays in registers between the passes over the row (it is the whole row up
+    // to K = 4096); later trips are fetched from LDS again.
+    int sums = 0; // block sums taken so far: selects the partials' buffer
     auto stage_row = [&](int mm) {
+        float v0[8];
+        const bool has0 = tid < chunks;
+        if (has0)
+            fetch(0, v0, true);
         float inv1 = 1.0f, inv2 = 1.0f;
         if constexpr (MODE != 0) {
-            inv1 = 1.0f / sqrtf(gemv_block_sum(squares(false, 1.0f), part) / (float)K + 1e-5f);
+            // sum of squares of the row; second: of the fp16 result of the first rms
+            auto squares = [&](bool second) {
+                float ss = 0.f;
+                auto add = [&](const float (&v)[8]) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const float y = second ? (float)(_Float16)(v[e] * inv1) : v[e];
+                        ss += y * y;
+                    }
+                };
+                if (has0)
+                    add(v0);
+                for (int t = 1; t < trips; ++t)
+                    if (tid + STEP * t < chunks) {
+                        float v[8];
+                        fetch(t, v, !second);
+                        add(v);
+                    }
+                return ss;
+            };
+            inv1 = 1.0f / sqrtf(gemv_block_sum(squares(false), part, sums++ & 1) / (float)K + 1e-5f);
             if constexpr (MODE == 5) // rms twice: the first result is the stored fp16 block output
-                inv2 = 1.0f / sqrtf(gemv_block_sum(squares(true, inv1), part) / (float)K + 1e-5f);
+                inv2 = 1.0f / sqrtf(gemv_block_sum(squares(true), part, sums++ & 1) / (float)K + 1e-5f);
         }
-        for (int t = 0; t < trips; ++t) {
-            const int kc = tid + STEP * t;
-            if (kc < chunks) { // the 16 lanes that share a group agree: chunks is a multiple of 16
-                float v[8];
-                fetch(t, v, false);
-                if constexpr (MODE == 5) {
+        // writes one chunk of x to LDS, and the group sums (the 16 lanes that share a group are all here:
+        // chunks is a multiple of 16)
+        auto put = [&](int kc, float (&v)[8]) {
+            if constexpr (MODE == 5) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    v[e] = (float)(_Float16)(v[e] * inv1);
+            }
+            if constexpr (MODE == 3 || MODE == 5) {
+                if (blockIdx.x == 0) {
+                    h8 o;
 #pragma unroll
                     for (int e = 0; e < 8; ++e)
-                        v[e] = (float)(_Float16)(v[e] * inv1);
-                }
-                if constexpr (MODE == 3 || MODE == 5) {
-                    if (blockIdx.x == 0) {
-                        h8 o;
-#pragma unroll
-                        for (int e = 0; e < 8; ++e)
-                            o[e] = (_Float16)v[e]; // exact: already fp16 values
-                        *reinterpret_cast<h8 *>(in.aux + (size_t)mm * K + (size_t)kc * 8) = o;
-                    }
-                }
-                const float inv = MODE == 5 ? inv2 : inv1;
-                const int s = (kc >> 2) & 3;
-                h8 w;
-                float sx = 0.f, sc = 0.f;
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const float xe = MODE == 0 ? v[e] : (float)(_Float16)(v[e] * inv);
-                    w[e] = (_Float16)(xe * stage_factor<BITS>(s, e));
-                    sx += xe;
-                    sc += (float)w[e];
-                }
-                xl[(size_t)kc * M + mm] = w;
-                sx = row16_sum(sx);
-                sc = row16_sum(sc);
-                if ((kc & 15) == 0) {
-                    xsum[(kc >> 4) * M + mm] = sx;
-                    csum[(kc >> 4) * M + mm] = 1024.0f * sc;
+                        o[e] = (_Float16)v[e]; // exact: already fp16 values
+                    *reinterpret_cast<h8 *>(in.aux + (size_t)mm * K + (size_t)kc * 8) = o;
                 }
             }
-        }
+            const float inv = MODE == 5 ? inv2 : inv1;
+            const int s = (kc >> 2) & 3;
+            h8 w;
+            float sx = 0.f, sc = 0.f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float xe = MODE == 0 ? v[e] : (float)(_Float16)(v[e] * inv);
+                w[e] = (_Float16)(xe * stage_factor<BITS>(s, e));
+                sx += xe;
+                sc += (float)w[e];
+            }
+            xl[(size_t)kc * M + mm] = w;
+            sx = row16_sum(sx);
+            sc = row16_sum(sc);
+            if ((kc & 15) == 0) {
+                xsum[(kc >> 4) * 16 + mm] = sx;
+                csum[(kc >> 4) * 16 + mm] = 1024.0f * sc;
+            }
+        };
+        if (has0)
+            put(tid, v0);
+        for (int t = 1; t < trips; ++t)
+            if (tid + STEP * t < chunks) {
+                float v[8];
+                fetch(t, v, false);
+                put(tid + STEP * t, v);
+            }
     };
     // Row 0 apart from the others: its copies were issued before the weights, so waiting for them leaves
     // the weights in flight; later rows are fetched behind the weights and wait for everything.
     __builtin_amdgcn_s_waitcnt(gemv_wait_vmcnt(RING_LOADS)); // the copies of row 0 have landed ...
     lds_barrier();                                           // ... in every wavefront
+    // Zero what no row writes: the groups past K (items on them then add nothing) and the sums of the
+    // activation rows past M.
+    for (int i = chunks * M + tid; i < GP * 16 * M; i += STEP)
+        xl[i] = h8{0, 0, 0, 0, 0, 0, 0, 0};
+    for (int i = tid; i < GP * 16; i += STEP)
+        if ((i & 15) >= M || (i >> 4) >= G) {
+            xsum[i] = 0.f;
+            csum[i] = 0.f;
+        }
     stage_row(0);
     for (int mm = 1; mm < M; ++mm) {
         lds_barrier(); // every thread is done with the previous row
@@ -432,33 +472,49 @@ __device__ __forceinline__ void gemv_body(const GemvJob job, int bj, const GemvI
     }
     lds_barrier(); // x is staged; the raw row (which shares LDS with the reduction buffers) is dead
 
-    f4 acc[SUB];
+    float acc[SUB][MV];
 #pragma unroll
     for (int u = 0; u < SUB; ++u)
-        acc[u] = f4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int v = 0; v < MV; ++v)
+            acc[u][v] = 0.f;
 
-    const bool live = m < M;
-    const int mc = min(m, M - 1), xlane = c * M + mc;
+    // The activations are the A operand (rows = activation rows m), the packed weights the B operand
+    // (columns = weight rows n): lane l receives D[m = 4*(l/16) + v][n = l%16], so one scale and one zero
+    // per lane and sub-block finish its results, and with M == 1 only v = 0 is needed at all.
+    // (the lane's coordinates are taken afresh here: carried across the staging they cost registers there)
+    int lane2 = threadIdx.x & 63;
+    asm volatile("" : "+v"(lane2));
+    const int m = lane2 & 15, c = lane2 >> 4;
+    const int mc = min(m, M - 1), xlane = c * M + mc; // lanes of unused A rows (m >= M) repeat row M-1
     GemvCursor cur = {bj, 0};
     int parity = 0;
     while (cur.rb < NRB) {
 #pragma unroll
         for (int d = 0; d < D; ++d) {
-            // No branch around the item: past the end of a row (or of the matrix) the slot holds a clamped
-            // reload, the item runs on it and its contribution is multiplied by zero.  With a branch, the
-            // compiler could not tell how many loads are in flight and waited for all of them.
+            // No branch around the item: past the end of a row the slot holds a clamped reload and the
+            // item runs on it against the zeroed groups of x; past the last row its results are dropped.
+            // With a branch, the compiler could not tell how many loads are in flight and waited for all.
             const int g = wave + GNW * cur.t;
-            const bool valid = (cur.rb < NRB) && (g < G);
-            const int gc = min(g, G - 1);
             {
-                // lanes of the unused MFMA columns (m >= M) repeat column M-1; their results are never stored
-                const h8 *xg_ptr = xl + (size_t)gc * 16 * M + xlane;
-                h8 bx[4];
+                const h8 *xg_ptr = xl + (size_t)g * 16 * M + xlane;
+                h8 ax[4];
 #pragma unroll
                 for (int s = 0; s < 4; ++s)
-                    bx[s] = xg_ptr[s * 4 * M];
-                const float xg = xsum[gc * M + mc], ncg = -csum[gc * M + mc];
-                const float keep = valid ? 1.0f : 0.0f;
+                    ax[s] = xg_ptr[s * 4 * M];
+                float xg[MV], cg[MV];
+                if constexpr (MV == 4) {
+                    const f4 a4 = *reinterpret_cast<const f4 *>(xsum + g * 16 + 4 * c);
+                    const f4 c4 = *reinterpret_cast<const f4 *>(csum + g * 16 + 4 * c);
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        xg[v] = a4[v];
+                        cg[v] = c4[v];
+                    }
+                } else {
+                    xg[0] = xsum[g * 16];
+                    cg[0] = csum[g * 16];
+                }
                 uint32_t dw[4 * Fmt<BITS>::PLANES];
 #pragma unroll
                 for (int p = 0; p < Fmt<BITS>::PLANES; ++p) {
@@ -472,38 +528,37 @@ __device__ __forceinline__ void gemv_body(const GemvJob job, int bj, const GemvI
                     for (int i = 0; i < BITS; ++i)
                         C[i] = dw[BITS * u + i];
                     extract_biased<BITS>(C, h);
-                    f4 p = {ncg, ncg, ncg, ncg}; // the bias term leaves with the accumulator's start value
+                    f4 p = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                     for (int s = 0; s < 4; ++s)
-                        p = mfma16x16x32(make_h8_bits(h[4 * s], h[4 * s + 1], h[4 * s + 2], h[4 * s + 3]), bx[s], p);
+                        p = mfma16x16x32(ax[s], make_h8_bits(h[4 * s], h[4 * s + 1], h[4 * s + 2], h[4 * s + 3]), p);
+                    // p = sum x code + 1024 sum x': take the bias and zero * sum x away, then scale
+                    const float zf = (float)ring[d].zero[u], sf = (float)ring[d].scale[u];
 #pragma unroll
-                    for (int v = 0; v < 4; ++v) {
-                        const float t = fmaf(-(float)ring[d].zero[u][v], xg, p[v]);
-                        acc[u][v] = fmaf((float)ring[d].scale[u][v] * keep, t, acc[u][v]);
-                    }
+                    for (int v = 0; v < MV; ++v)
+                        acc[u][v] = fmaf(sf, p[v] - fmaf(zf, xg[v], cg[v]), acc[u][v]);
                 }
             }
             issue(ring[d]); // the item D places ahead reuses this slot
             if (cur.rb < NRB && ++cur.t == T) {
                 // end of a supertile row: fixed-order reduction over the wavefronts, double-buffered
-                float *rbuf = red + (size_t)parity * GNW * SUB * 4 * 64;
+                float *rbuf = red + (size_t)parity * GNW * SUB * MV * 64;
 #pragma unroll
                 for (int u = 0; u < SUB; ++u)
 #pragma unroll
-                    for (int v = 0; v < 4; ++v) {
-                        rbuf[(wave * SUB * 4 + u * 4 + v) * 64 + lane] = acc[u][v];
+                    for (int v = 0; v < MV; ++v) {
+                        rbuf[(wave * SUB * MV + u * MV + v) * 64 + lane] = acc[u][v];
                         acc[u][v] = 0.f;
                     }
                 lds_barrier();
-                if (live) {
-                    for (int e = wave; e < SUB * 4; e += GNW) {
+                for (int e = wave; e < SUB * MV; e += GNW) {
+                    const int mrow = 4 * c + (e % MV), n = cur.rb * ROWS + 16 * (e / MV) + (lane & 15);
+                    if (mrow < M && n < job.N) {
                         float sum = 0.f;
 #pragma unroll
                         for (int w = 0; w < GNW; ++w)
-                            sum += rbuf[(w * SUB * 4 + e) * 64 + lane];
-                        const int n = cur.rb * ROWS + 16 * (e >> 2) + 4 * c + (e & 3);
-                        if (n < job.N)
-                            job.out[(size_t)m * job.N + n] = (_Float16)sum;
+                            sum += rbuf[(w * SUB * MV + e) * 64 + lane];
+                        job.out[(size_t)mrow * job.N + n] = (_Float16)sum;
                     }
                 }
                 cur.t = 0;
@@ -515,11 +570,11 @@ __device__ __forceinline__ void gemv_body(const GemvJob job, int bj, const GemvI
 }
 
 // Four wavefronts per SIMD, i.e. two workgroups per CU.
-template <int MODE>
+template <int MODE, int MV>
 __global__ __launch_bounds__(64 * GNW, 4) void gemv_stream_kernel(GemvInput in, int M, int K, GemvJobs jobs)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    __shared__ float part[GNW];
+    __shared__ float part[2 * GNW];
     // the job of this workgroup, selected by value so that its fields stay in scalar registers
     GemvJob job = jobs.j[0];
     if (jobs.count > 1 && (int)blockIdx.x >= jobs.j[1].blk0)
@@ -528,32 +583,40 @@ __global__ __launch_bounds__(64 * GNW, 4) void gemv_stream_kernel(GemvInput in, 
         job = jobs.j[2];
     const int bj = blockIdx.x - job.blk0;
     switch (job.bits) { // uniform across the workgroup
-    case 2: gemv_body<2, MODE>(job, bj, in, M, K, smem, part); break;
-    case 3: gemv_body<3, MODE>(job, bj, in, M, K, smem, part); break;
-    case 4: gemv_body<4, MODE>(job, bj, in, M, K, smem, part); break;
-    default: gemv_body<8, MODE>(job, bj, in, M, K, smem, part); break;
+    case 2: gemv_body<2, MODE, MV>(job, bj, in, M, K, smem, part); break;
+    case 3: gemv_body<3, MODE, MV>(job, bj, in, M, K, smem, part); break;
+    case 4: gemv_body<4, MODE, MV>(job, bj, in, M, K, smem, part); break;
+    default: gemv_body<8, MODE, MV>(job, bj, in, M, K, smem, part); break;
     }
 }
 
 typedef void (*GemvKernel)(GemvInput, int, int, GemvJobs);
 
-GemvKernel gemv_kernel_for(int mode)
+// One kernel per input mode, for a single activation row and for up to sixteen.
+GemvKernel gemv_kernel_for(int mode, int M, int *slot)
 {
-    static const GemvKernel table[6] = {gemv_stream_kernel<0>, gemv_stream_kernel<1>, gemv_stream_kernel<2>,
-                                        gemv_stream_kernel<3>, gemv_stream_kernel<4>, gemv_stream_kernel<5>};
-    return table[mode];
+    static const GemvKernel table[6][2] = {
+        {gemv_stream_kernel<0, 1>, gemv_stream_kernel<0, 4>}, {gemv_stream_kernel<1, 1>, gemv_stream_kernel<1, 4>},
+        {gemv_stream_kernel<2, 1>, gemv_stream_kernel<2, 4>}, {gemv_stream_kernel<3, 1>, gemv_stream_kernel<3, 4>},
+        {gemv_stream_kernel<4, 1>, gemv_stream_kernel<4, 4>}, {gemv_stream_kernel<5, 1>, gemv_stream_kernel<5, 4>},
+    };
+    const int wide = M == 1 ? 0 : 1;
+    *slot = 2 * mode + wide;
+    return table[mode][wide];
 }
 
 constexpr size_t GEMV_MAX_LDS = 152 * 1024;
 
-// Dynamic LDS of a streaming launch: staged x, the group sums, and one region shared by the raw input
-// row (inputs of the mode, whole trips of 512 chunks) and the reduction buffers.
+// Dynamic LDS of a streaming launch: staged x and the group sums (groups rounded up to whole turns of
+// the wavefronts), and one region shared by the raw input row (inputs of the mode, whole trips of 512
+// chunks) and the reduction buffers.
 size_t gemv_stream_lds(int M, int K, int bits, int inputs)
 {
-    const int sub = bits == 3 ? 4 : (bits == 2 ? 2 : 1);
-    const size_t red = 2 * (size_t)GNW * sub * 4 * 64 * 4;
+    const int sub = bits == 3 ? 4 : (bits == 2 ? 2 : 1), mv = M == 1 ? 1 : 4;
+    const size_t gp = (size_t)(((K >> 7) + GNW - 1) / GNW) * GNW;
+    const size_t red = 2 * (size_t)GNW * sub * mv * 64 * 4;
     const size_t raw = (size_t)inputs * (((K >> 3) + 64 * GNW - 1) / (64 * GNW)) * (64 * GNW) * 16;
-    return (size_t)M * K * 2 + 2 * (size_t)(K >> 7) * M * 4 + (red > raw ? red : raw);
+    return gp * 16 * M * 16 + 2 * gp * 16 * 4 + (red > raw ? red : raw);
 }
 
 int rows_per_supertile(int bits) { return bits == 2 ? 32 : (bits == 3 ? 64 : 16); }
@@ -562,7 +625,7 @@ int rows_per_supertile(int bits) { return bits == 2 ? 32 : (bits == 3 ? 64 : 16)
 int gemv_resident_blocks(GemvKernel kernel, int slot, size_t lds, int *out)
 {
     static int cus = 0;
-    static bool prepared[6];
+    static bool prepared[12];
     if (cus == 0) {
         int dev = 0, n = 0;
         hipError_t e = hipGetDevice(&dev);
@@ -581,8 +644,8 @@ int gemv_resident_blocks(GemvKernel kernel, int slot, size_t lds, int *out)
         prepared[slot] = true;
     }
     // the answer depends only on the kernel and the LDS request: remember the last few
-    static size_t seen_lds[6][4];
-    static int seen_blocks[6][4], seen[6];
+    static size_t seen_lds[12][4];
+    static int seen_blocks[12][4], seen[12];
     for (int i = 0; i < seen[slot]; ++i)
         if (seen_lds[slot][i] == lds) {
             *out = seen_blocks[slot][i];
@@ -627,9 +690,9 @@ int fq_launch_gemv_multi(const fq_gemv_input &src, int M, const fq_packed_ref *w
         bytes[i] = (double)w[i].N * w[i].K * w[i].bits;
         total += bytes[i];
     }
-    int resident = 0;
-    const GemvKernel kernel = gemv_kernel_for(src.mode);
-    if (int e = gemv_resident_blocks(kernel, src.mode, lds, &resident))
+    int slot = 0, resident = 0;
+    const GemvKernel kernel = gemv_kernel_for(src.mode, M, &slot);
+    if (int e = gemv_resident_blocks(kernel, slot, lds, &resident))
         return e;
     int grid = sum_nrb < resident ? sum_nrb : resident;
     if (grid < count)
