@@ -142,6 +142,7 @@ struct GemvJob {
     _Float16 *out;
     int N, bits;
     int blk0, nblk; // the workgroups [blk0, blk0 + nblk) of the launch serve this matrix
+    int split;      // 2- and 3-bit only: work units are the 16-row sub-blocks of a supertile row, not whole rows
 };
 
 struct GemvJobs {
@@ -201,10 +202,15 @@ __device__ __forceinline__ float gemv_block_sum(float v, float *part, int which)
     return sum;
 }
 
-template <int BITS>
+// One (work unit, group) item in flight: the packed dwords a lane owns and its scale and zero.  A unit
+// is S sub-blocks of 16 weight rows: a whole supertile row (whole planes, 128-bit loads), or a single
+// sub-block of a 2- or 3-bit supertile row (just its BITS dwords).
+template <int BITS, int S>
 struct GemvSlot {
-    u4v plane[Fmt<BITS>::PLANES];
-    _Float16 scale[Fmt<BITS>::SUB], zero[Fmt<BITS>::SUB]; // of weight row lane % 16 of each sub-block
+    static constexpr bool WHOLE = S == Fmt<BITS>::SUB;
+    u4v plane[WHOLE ? Fmt<BITS>::PLANES : 1];
+    uint32_t w[WHOLE ? 1 : BITS];
+    _Float16 scale[S], zero[S]; // of weight row lane % 16 of each sub-block
 };
 
 // 2^-pair_shift for element e of k-step s: the factor applied to x while staging.
@@ -225,9 +231,9 @@ __device__ __forceinline__ float stage_factor(int s, int e)
     }
 }
 
-// Position in the stream of (supertile row, group) items of one wavefront.
+// Position in the stream of (work unit, group) items of one wavefront.
 struct GemvCursor {
-    int rb, t; // supertile row, t-th group of this wavefront in it
+    int ub, t; // work unit, t-th group of this wavefront in it
 };
 
 // Inputs the transform of each mode reads.
@@ -257,7 +263,10 @@ __device__ __forceinline__ void gemv_combine(const h8 (&r)[GemvInputs<MODE>::N],
 constexpr int gemv_wait_vmcnt(int n) { return 0x0f70 | (n & 15) | ((n >> 4) << 14); }
 
 // MV: activation rows a lane finishes per sub-block (1 when M == 1, else 4).
-template <int BITS, int MODE, int MV>
+// S: sub-blocks per work unit (all of a supertile row's, or 1).  With F = SUB/S units per supertile row,
+// unit ub is part (ub/8) % F of supertile row (ub / (8F)) * 8 + ub % 8: the F workgroups that share a
+// supertile row (and read the same cache lines) are 8 apart, i.e. on the same XCD and L2.
+template <int BITS, int MODE, int MV, int S>
 __device__ __forceinline__ void gemv_body(const GemvJob job, int bj, const GemvInput in, int M, int K,
                                           unsigned char *smem, float *part)
 {
@@ -265,7 +274,9 @@ __device__ __forceinline__ void gemv_body(const GemvJob job, int bj, const GemvI
     constexpr int NIN = GemvInputs<MODE>::N, STEP = 64 * GNW;
     // vector loads one fill of the ring issues: planes, scales and zeros of every slot (none of them
     // can merge: they are at least a kilobyte apart or come from different arrays)
-    constexpr int RING_LOADS = D * (Fmt<BITS>::PLANES + 2 * SUB);
+    constexpr int F = SUB / S;
+    constexpr bool WHOLE = F == 1;
+    constexpr int RING_LOADS = D * ((WHOLE ? Fmt<BITS>::PLANES : (BITS == 2 ? 1 : BITS)) + 2 * S);
     static_assert(RING_LOADS < 64, "the wait below counts the ring's loads");
     const int G = K >> 7;
     const int T = (G + GNW - 1) / GNW; // groups per wavefront and supertile row
@@ -273,18 +284,21 @@ __device__ __forceinline__ void gemv_body(const GemvJob job, int bj, const GemvI
     h8 *xl = reinterpret_cast<h8 *>(smem);                                   // [GP*16][M] staged activations
     float *xsum = reinterpret_cast<float *>(smem + (size_t)GP * 16 * M * 16); // [GP][16] sum of x over the group
     float *csum = xsum + (size_t)GP * 16;                                    // [GP][16] 1024 * sum of staged x
-    float *red = csum + (size_t)GP * 16;                                     // [2][GNW][SUB*MV][64]
+    float *red = csum + (size_t)GP * 16;                                     // [2][GNW][S*MV][64]
     h8 *raw = reinterpret_cast<h8 *>(red); // [NIN][trips][STEP] raw input row; free again before the first reduction
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6); // scalar: keeps tile addressing in SGPRs
     const int NRB = ((job.N + 63) / 64 * 64) / ROWS;
+    const int NU = WHOLE ? NRB : (NRB + 7) / 8 * 8 * F; // work units (with F > 1 some may lie past the matrix)
     const int nblk = job.nblk;
     const uint32_t *const packed = job.packed;
     const _Float16 *const scales = job.scales, *const zeros = job.zeros;
 
-    if (bj >= NRB)
+    if (bj >= NU)
         return; // uniform: nothing to do for this workgroup
+    auto unit_row = [&](int ub) { return WHOLE ? ub : (ub / (8 * F)) * 8 + (ub & 7); };
+    auto unit_part = [&](int ub) { return WHOLE ? 0 : (ub >> 3) & (F - 1); };
 
     // ---- the input row first, copied from global memory straight into LDS (no registers): the
     // staging below then waits for these copies only, not for the weights issued behind them.  The
@@ -302,33 +316,52 @@ __device__ __forceinline__ void gemv_body(const GemvJob job, int bj, const GemvI
 
     // ---- weights: unconditional loads (indices clamped into the matrix) so that a wavefront only
     // ever waits for the oldest slot of its ring.
-    GemvSlot<BITS> ring[D];
-    GemvCursor pre = {bj, 0};
-    // Addresses: a per-row base, recomputed when the stream moves to the next supertile row, plus a
-    // 32-bit offset for the group, plus the lane's own offset.
+    // Addresses: a per-unit base, recomputed when the stream moves to the next unit, plus a 32-bit
+    // offset for the group, plus the lane's own offset.  Units past the end read supertile row 0.
     const uint32_t plane_off = (uint32_t)lane * 4u, meta_off = (uint32_t)(lane & 15);
-    const size_t row_tiles = (size_t)G * TILE, row_meta = (size_t)G * 16 * SUB; // per supertile row
-    const uint32_t *tile_row = packed + (size_t)bj * row_tiles;
-    const _Float16 *scale_row = scales + (size_t)bj * row_meta, *zero_row = zeros + (size_t)bj * row_meta;
-    auto issue = [&](GemvSlot<BITS> &sl) {
+    const size_t row_tiles = (size_t)G * TILE;
+    const uint32_t *tile_row;
+    const _Float16 *scale_row, *zero_row;
+    int pre_part;
+    auto set_unit = [&](int ub) {
+        const int r = unit_row(ub), rb = (ub < NU && r < NRB) ? r : 0;
+        pre_part = unit_part(ub);
+        tile_row = packed + (size_t)rb * row_tiles;
+        const size_t meta = (size_t)(rb * SUB + pre_part * S) * G * 16;
+        scale_row = scales + meta;
+        zero_row = zeros + meta;
+    };
+    GemvSlot<BITS, S> ring[D];
+    GemvCursor pre = {bj, 0};
+    set_unit(bj);
+    auto issue = [&](GemvSlot<BITS, S> &sl) {
         const uint32_t g = (uint32_t)min(wave + GNW * pre.t, G - 1);
         const uint32_t *tile = tile_row + g * (uint32_t)TILE;
+        if constexpr (WHOLE) {
 #pragma unroll
-        for (int p = 0; p < Fmt<BITS>::PLANES; ++p)
-            sl.plane[p] = *reinterpret_cast<const u4v *>(tile + p * 256 + plane_off);
+            for (int p = 0; p < Fmt<BITS>::PLANES; ++p)
+                sl.plane[p] = *reinterpret_cast<const u4v *>(tile + p * 256 + plane_off);
+        } else if constexpr (BITS == 2) {
+            const u2v v = *reinterpret_cast<const u2v *>(tile + plane_off + 2 * pre_part);
+            sl.w[0] = v.x;
+            sl.w[1] = v.y;
+        } else {
 #pragma unroll
-        for (int u = 0; u < SUB; ++u) {
+            for (int i = 0; i < BITS; ++i) {
+                const int j = BITS * pre_part + i; // dword j of the lane: plane j / 4, component j % 4
+                sl.w[i] = tile[(j >> 2) * 256 + plane_off + (j & 3)];
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < S; ++u) {
             const uint32_t meta = ((uint32_t)u * (uint32_t)G + g) * 16u;
             sl.scale[u] = scale_row[meta + meta_off];
             sl.zero[u] = zero_row[meta + meta_off];
         }
         if (++pre.t == T) {
             pre.t = 0;
-            pre.rb += nblk;
-            const int rb = pre.rb < NRB ? pre.rb : bj; // past the end: any row of ours, the data is not used
-            tile_row = packed + (size_t)rb * row_tiles;
-            scale_row = scales + (size_t)rb * row_meta;
-            zero_row = zeros + (size_t)rb * row_meta;
+            pre.ub += nblk;
+            set_unit(pre.ub);
         }
     };
 #pragma unroll
@@ -472,9 +505,9 @@ __device__ __forceinline__ void gemv_body(const GemvJob job, int bj, const GemvI
     }
     lds_barrier(); // x is staged; the raw row (which shares LDS with the reduction buffers) is dead
 
-    float acc[SUB][MV];
+    float acc[S][MV];
 #pragma unroll
-    for (int u = 0; u < SUB; ++u)
+    for (int u = 0; u < S; ++u)
 #pragma unroll
         for (int v = 0; v < MV; ++v)
             acc[u][v] = 0.f;
@@ -489,7 +522,7 @@ __device__ __forceinline__ void gemv_body(const GemvJob job, int bj, const GemvI
     const int mc = min(m, M - 1), xlane = c * M + mc; // lanes of unused A rows (m >= M) repeat row M-1
     GemvCursor cur = {bj, 0};
     int parity = 0;
-    while (cur.rb < NRB) {
+    while (cur.ub < NU) {
 #pragma unroll
         for (int d = 0; d < D; ++d) {
             // No branch around the item: past the end of a row the slot holds a clamped reload and the
@@ -515,18 +548,21 @@ __device__ __forceinline__ void gemv_body(const GemvJob job, int bj, const GemvI
                     xg[0] = xsum[g * 16];
                     cg[0] = csum[g * 16];
                 }
-                uint32_t dw[4 * Fmt<BITS>::PLANES];
 #pragma unroll
-                for (int p = 0; p < Fmt<BITS>::PLANES; ++p) {
-                    dw[4 * p + 0] = ring[d].plane[p].x; dw[4 * p + 1] = ring[d].plane[p].y;
-                    dw[4 * p + 2] = ring[d].plane[p].z; dw[4 * p + 3] = ring[d].plane[p].w;
-                }
-#pragma unroll
-                for (int u = 0; u < SUB; ++u) {
+                for (int u = 0; u < S; ++u) {
                     uint32_t C[BITS], h[16];
+                    if constexpr (WHOLE) {
 #pragma unroll
-                    for (int i = 0; i < BITS; ++i)
-                        C[i] = dw[BITS * u + i];
+                        for (int i = 0; i < BITS; ++i) {
+                            const int j = BITS * u + i;
+                            const u4v pl = ring[d].plane[j >> 2];
+                            C[i] = (j & 3) == 0 ? pl.x : ((j & 3) == 1 ? pl.y : ((j & 3) == 2 ? pl.z : pl.w));
+                        }
+                    } else {
+#pragma unroll
+                        for (int i = 0; i < BITS; ++i)
+                            C[i] = ring[d].w[i];
+                    }
                     extract_biased<BITS>(C, h);
                     f4 p = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -540,29 +576,30 @@ __device__ __forceinline__ void gemv_body(const GemvJob job, int bj, const GemvI
                 }
             }
             issue(ring[d]); // the item D places ahead reuses this slot
-            if (cur.rb < NRB && ++cur.t == T) {
-                // end of a supertile row: fixed-order reduction over the wavefronts, double-buffered
-                float *rbuf = red + (size_t)parity * GNW * SUB * MV * 64;
+            if (cur.ub < NU && ++cur.t == T) {
+                // end of a unit: fixed-order reduction over the wavefronts, double-buffered
+                float *rbuf = red + (size_t)parity * GNW * S * MV * 64;
 #pragma unroll
-                for (int u = 0; u < SUB; ++u)
+                for (int u = 0; u < S; ++u)
 #pragma unroll
                     for (int v = 0; v < MV; ++v) {
-                        rbuf[(wave * SUB * MV + u * MV + v) * 64 + lane] = acc[u][v];
+                        rbuf[(wave * S * MV + u * MV + v) * 64 + lane] = acc[u][v];
                         acc[u][v] = 0.f;
                     }
                 lds_barrier();
-                for (int e = wave; e < SUB * MV; e += GNW) {
-                    const int mrow = 4 * c + (e % MV), n = cur.rb * ROWS + 16 * (e / MV) + (lane & 15);
-                    if (mrow < M && n < job.N) {
+                const int n0 = unit_row(cur.ub) * ROWS + 16 * S * unit_part(cur.ub) + (lane & 15);
+                for (int e = wave; e < S * MV; e += GNW) {
+                    const int mrow = 4 * c + (e % MV), n = n0 + 16 * (e / MV);
+                    if (mrow < M && n < job.N) { // units past the matrix have n >= N
                         float sum = 0.f;
 #pragma unroll
                         for (int w = 0; w < GNW; ++w)
-                            sum += rbuf[(w * SUB * MV + e) * 64 + lane];
+                            sum += rbuf[(w * S * MV + e) * 64 + lane];
                         job.out[(size_t)mrow * job.N + n] = (_Float16)sum;
                     }
                 }
                 cur.t = 0;
-                cur.rb += nblk;
+                cur.ub += nblk;
                 parity ^= 1;
             }
         }
@@ -583,10 +620,20 @@ __global__ __launch_bounds__(64 * GNW, 4) void gemv_stream_kernel(GemvInput in, 
         job = jobs.j[2];
     const int bj = blockIdx.x - job.blk0;
     switch (job.bits) { // uniform across the workgroup
-    case 2: gemv_body<2, MODE, MV>(job, bj, in, M, K, smem, part); break;
-    case 3: gemv_body<3, MODE, MV>(job, bj, in, M, K, smem, part); break;
-    case 4: gemv_body<4, MODE, MV>(job, bj, in, M, K, smem, part); break;
-    default: gemv_body<8, MODE, MV>(job, bj, in, M, K, smem, part); break;
+    case 2:
+        if (job.split)
+            gemv_body<2, MODE, MV, 1>(job, bj, in, M, K, smem, part);
+        else
+            gemv_body<2, MODE, MV, 2>(job, bj, in, M, K, smem, part);
+        break;
+    case 3:
+        if (job.split)
+            gemv_body<3, MODE, MV, 1>(job, bj, in, M, K, smem, part);
+        else
+            gemv_body<3, MODE, MV, 4>(job, bj, in, M, K, smem, part);
+        break;
+    case 4: gemv_body<4, MODE, MV, 1>(job, bj, in, M, K, smem, part); break;
+    default: gemv_body<8, MODE, MV, 1>(job, bj, in, M, K, smem, part); break;
     }
 }
 
@@ -694,6 +741,25 @@ int fq_launch_gemv_multi(const fq_gemv_input &src, int M, const fq_packed_ref *w
     const GemvKernel kernel = gemv_kernel_for(src.mode, M, &slot);
     if (int e = gemv_resident_blocks(kernel, slot, lds, &resident))
         return e;
+    // A lone 2- or 3-bit matrix with so few supertile rows that half the chip would idle is handed out
+    // by 16-row sub-blocks instead (2 or 4 per supertile row).  The workgroups that then share a
+    // supertile row run at the same time on one XCD, so its L2 fetches their common lines once.
+    if (count == 1 && (w[0].bits == 2 || w[0].bits == 3) && 2 * nrb[0] <= resident) {
+        const int parts = w[0].bits == 2 ? 2 : 4;
+        const int units = (nrb[0] + 7) / 8 * 8 * parts;
+        int nb = (units < resident ? units : resident) / 8 * 8;
+        if (nb < 8)
+            nb = 8;
+        jobs.j[0] = GemvJob{static_cast<const uint32_t *>(w[0].packed), static_cast<const _Float16 *>(w[0].scales),
+                            static_cast<const _Float16 *>(w[0].zeros), static_cast<_Float16 *>(outs[0]), w[0].N,
+                            w[0].bits, 0, nb, 1};
+        for (int i = 1; i < 3; ++i)
+            jobs.j[i] = GemvJob{nullptr, nullptr, nullptr, nullptr, 0, 0, nb, 0, 0};
+        const GemvInput in = {static_cast<const _Float16 *>(src.a), static_cast<const _Float16 *>(src.b),
+                              static_cast<const _Float16 *>(src.c), static_cast<_Float16 *>(src.aux), src.mode};
+        hipLaunchKernelGGL(kernel, dim3(nb), dim3(64 * GNW), lds, st, in, M, w[0].K, jobs);
+        return (int)hipGetLastError();
+    }
     int grid = sum_nrb < resident ? sum_nrb : resident;
     if (grid < count)
         grid = count;
@@ -710,12 +776,12 @@ int fq_launch_gemv_multi(const fq_gemv_input &src, int M, const fq_packed_ref *w
             nb = 1;
         jobs.j[i] = GemvJob{static_cast<const uint32_t *>(w[i].packed), static_cast<const _Float16 *>(w[i].scales),
                             static_cast<const _Float16 *>(w[i].zeros), static_cast<_Float16 *>(outs[i]), w[i].N,
-                            w[i].bits, blk0, nb};
+                            w[i].bits, blk0, nb, 0};
         blk0 += nb;
         left -= nb;
     }
     for (int i = count; i < 3; ++i)
-        jobs.j[i] = GemvJob{nullptr, nullptr, nullptr, nullptr, 0, 0, blk0, 0};
+        jobs.j[i] = GemvJob{nullptr, nullptr, nullptr, nullptr, 0, 0, blk0, 0, 0};
     const GemvInput in = {static_cast<const _Float16 *>(src.a), static_cast<const _Float16 *>(src.b),
                           static_cast<const _Float16 *>(src.c), static_cast<_Float16 *>(src.aux), src.mode};
     hipLaunchKernelGGL(kernel, dim3(blk0), dim3(64 * GNW), lds, st, in, M, w[0].K, jobs);
