@@ -121,7 +121,9 @@ int fq_dequant(const void *packed, const void *scales, const void *zeros,
  * device, written.  M <= 16 runs the bandwidth-bound streaming kernel (decode),
  * larger M the matrix-core tile kernel (calibration forward).  Any M >= 1,
  * N >= 1.  Scales and zeros may be any finite fp16 (e.g. zero/2^d after
- * truncating d code bits, Section "Elastic Serving").
+ * truncating d code bits, Section "Elastic Serving").  For M > 16 the
+ * activations (M*K*2 bytes) and the packed weights must each stay below
+ * 4 GiB, else FQ_ERR_SHAPE.
  */
 int fq_qlinear(const void *x, int M, const void *packed, const void *scales, const void *zeros,
                int N, int K, int bits, int group, void *out, void *stream);
@@ -171,7 +173,8 @@ int fq_glue(int op, const void *a, const void *b, const void *c, int M, int H, v
 /*
  * Unquantized fp16 linear (the vocabulary head): out[m,n] = sum_k x[m,k] W[n,k],
  * fp32 accumulation, fp16 output.  x [M,K], W [N,K], out [M,N] row-major,
- * device.  K must be a multiple of 128.
+ * device.  K must be a multiple of 128; x and W must each stay below 4 GiB
+ * (FQ_ERR_SHAPE otherwise).
  */
 int fq_dense_f16(const void *x, int M, const void *W, int N, int K, void *out, void *stream);
 

@@ -34,8 +34,14 @@ int check_matrix(const char *fn, const void *packed, const void *scales, const v
     return FQ_OK;
 }
 
+// The M > 16 kernels address each array through 32-bit byte offsets.
+bool below_4gib(size_t a, size_t b, size_t elem_bytes) { return a * b * elem_bytes < ((size_t)1 << 32); }
+
 int qlinear_checked(const void *x, int M, const fq_packed_ref &w, void *out, fq_stream st)
 {
+    if (M > 16 && (!below_4gib(M, w.K, 2) || !below_4gib(((size_t)w.N + 63) / 64 * 8, w.K, w.bits)))
+        return fq_fail(FQ_ERR_SHAPE, "fq_qlinear: M=%d N=%d K=%d: activations and packed weights must each stay "
+                       "below 4 GiB", M, w.N, w.K);
     int e = (M <= 16) ? fq_launch_gemv(x, M, w, out, st) : fq_launch_gemm(x, M, w, out, st);
     return check_hip(e, "fq_qlinear launch");
 }
@@ -80,6 +86,8 @@ extern "C" int fq_dense_f16(const void *x, int M, const void *W, int N, int K, v
         return fq_fail(FQ_ERR_SHAPE, "fq_dense_f16: M=%d N=%d K=%d (K must be a positive multiple of 128)", M, N, K);
     if (!aligned16(x) || !aligned16(W) || !aligned16(out))
         return fq_fail(FQ_ERR_ALIGN, "fq_dense_f16: pointers must be 16-byte aligned");
+    if (!below_4gib(M, K, 2) || !below_4gib(N, K, 2))
+        return fq_fail(FQ_ERR_SHAPE, "fq_dense_f16: M=%d N=%d K=%d: x and W must each stay below 4 GiB", M, N, K);
     return check_hip(fq_launch_dense(x, M, W, N, K, out, static_cast<fq_stream>(stream)), "fq_dense_f16 launch");
 }
 

@@ -62,6 +62,62 @@ __device__ __forceinline__ void load_chunk(const uint32_t *tile, int u, int lane
     }
 }
 
+// ---------------------------------------------------------------------------
+// Buffer addressing: a 128-bit descriptor (base, size in bytes) in scalar registers, a scalar byte
+// offset and a 32-bit per-lane byte offset.  A load then costs no vector address arithmetic, and lanes
+// past the size read zero.  Every array addressed this way is smaller than 4 GiB (the callers check).
+// ---------------------------------------------------------------------------
+typedef __amdgpu_buffer_rsrc_t fq_rsrc;
+
+__device__ __forceinline__ fq_rsrc make_rsrc(const void *base, uint32_t bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, bytes, 0x00020000);
+}
+
+__device__ __forceinline__ u4v buf_load_b128(fq_rsrc r, uint32_t lane_off, uint32_t uniform_off)
+{
+    return __builtin_bit_cast(u4v, __builtin_amdgcn_raw_buffer_load_b128(r, lane_off, uniform_off, 0));
+}
+
+__device__ __forceinline__ u2v buf_load_b64(fq_rsrc r, uint32_t lane_off, uint32_t uniform_off)
+{
+    return __builtin_bit_cast(u2v, __builtin_amdgcn_raw_buffer_load_b64(r, lane_off, uniform_off, 0));
+}
+
+__device__ __forceinline__ uint32_t buf_load_b32(fq_rsrc r, uint32_t lane_off, uint32_t uniform_off)
+{
+    return __builtin_amdgcn_raw_buffer_load_b32(r, lane_off, uniform_off, 0);
+}
+
+// 16 bits, zero-extended
+__device__ __forceinline__ uint32_t buf_load_u16(fq_rsrc r, uint32_t lane_off, uint32_t uniform_off)
+{
+    return __builtin_amdgcn_raw_buffer_load_b16(r, lane_off, uniform_off, 0);
+}
+
+// The BITS dwords of sub-block `u` owned by `lane`, from the supertile at byte offset tile_off.
+template <int BITS>
+__device__ __forceinline__ void buf_load_chunk(fq_rsrc packed, uint32_t tile_off, int u, int lane, uint32_t (&C)[BITS])
+{
+    const uint32_t lo = (uint32_t)lane * 16u;
+    if constexpr (BITS == 4) {
+        const u4v v = buf_load_b128(packed, lo, tile_off);
+        C[0] = v.x; C[1] = v.y; C[2] = v.z; C[3] = v.w;
+    } else if constexpr (BITS == 8) {
+        const u4v a = buf_load_b128(packed, lo, tile_off);
+        const u4v b = buf_load_b128(packed, lo + 1024u, tile_off);
+        C[0] = a.x; C[1] = a.y; C[2] = a.z; C[3] = a.w;
+        C[4] = b.x; C[5] = b.y; C[6] = b.z; C[7] = b.w;
+    } else if constexpr (BITS == 2) {
+        const u2v v = buf_load_b64(packed, lo + 8u * (uint32_t)u, tile_off);
+        C[0] = v.x; C[1] = v.y;
+    } else {
+#pragma unroll
+        for (int i = 0; i < 3; ++i)
+            C[i] = buf_load_b32(packed, 4u * (uint32_t)lane_dword(3 * u + i, lane), tile_off);
+    }
+}
+
 // Plain integer code of element t = 8*s + e of a chunk: the format read literally.
 template <int BITS>
 __device__ __forceinline__ uint32_t code_at(const uint32_t (&C)[BITS], int t)

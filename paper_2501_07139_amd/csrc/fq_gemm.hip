@@ -33,7 +33,7 @@ constexpr int DENSE = 16; // BITS value of the unquantized fp16 weight path (the
 template <int BITS>
 struct WChunk {
     uint32_t c[BITS];
-    _Float16 scale, zero;
+    uint32_t scale, zero; // fp16 bits in the low half, as loaded: nothing touches them before their use
 };
 
 // fp16 weights: a lane's operands of the four k-steps, read straight from the row-major matrix
@@ -42,31 +42,32 @@ struct WChunk<DENSE> {
     h8 f[4];
 };
 
+// Descriptors of the kernel's arrays (see make_rsrc).
+struct GemmBuffers {
+    fq_rsrc x, packed, scales, zeros;
+};
+
 template <int BITS>
-__device__ __forceinline__ void load_wchunk(WChunk<BITS> &w, const uint32_t *__restrict__ packed,
-                                            const _Float16 *__restrict__ scales,
-                                            const _Float16 *__restrict__ zeros, int rb16, int Np16, int G, int g,
-                                            int lane)
+__device__ __forceinline__ void load_wchunk(WChunk<BITS> &w, const GemmBuffers &buf, int rb16, int Np16, int G, int K,
+                                            int g, int lane)
 {
     if constexpr (BITS == DENSE) {
         // packed is the fp16 matrix [N,K]; Np16 carries N here.  Rows past the end re-read the last row.
-        const _Float16 *W = reinterpret_cast<const _Float16 *>(packed);
         const int row = min(rb16 * 16 + (lane & 15), Np16 - 1);
-        const _Float16 *src = W + (size_t)row * (G * 128) + g * 128 + 8 * (lane >> 4);
+        const uint32_t lo = ((uint32_t)row * (uint32_t)K + 8u * (uint32_t)(lane >> 4)) * 2u;
 #pragma unroll
         for (int s = 0; s < 4; ++s)
-            w.f[s] = *reinterpret_cast<const h8 *>(src + 32 * s);
-        return;
+            w.f[s] = __builtin_bit_cast(h8, buf_load_b128(buf.packed, lo + 64u * s, (uint32_t)g * 256u));
     } else {
-    constexpr int SUB = Fmt<BITS>::SUB;
-    // blocks past the end of the matrix re-read the last block: their results are never stored, and
-    // loads without a branch keep the count of loads in flight known to the compiler
-    const int rb = min(rb16, Np16 - 1);
-    const uint32_t *tile = packed + ((size_t)(rb / SUB) * G + g) * tile_dwords<BITS>();
-    load_chunk<BITS>(tile, rb % SUB, lane, w.c);
-    const size_t meta = ((size_t)rb * G + g) * 16 + (lane & 15);
-    w.scale = scales[meta];
-    w.zero = zeros[meta];
+        constexpr int SUB = Fmt<BITS>::SUB;
+        // blocks past the end of the matrix re-read the last block: their results are never stored, and
+        // loads without a branch keep the count of loads in flight known to the compiler
+        const int rb = min(rb16, Np16 - 1);
+        const uint32_t tile_off = (uint32_t)((rb / SUB) * G + g) * (uint32_t)(tile_dwords<BITS>() * 4);
+        buf_load_chunk<BITS>(buf.packed, tile_off, rb % SUB, lane, w.c);
+        const uint32_t meta_off = (uint32_t)(rb * G + g) * 32u, lo = (uint32_t)(lane & 15) * 2u;
+        w.scale = buf_load_u16(buf.scales, lo, meta_off);
+        w.zero = buf_load_u16(buf.zeros, lo, meta_off);
     }
 }
 
@@ -102,11 +103,23 @@ __global__ __launch_bounds__(256, 2) void qgemm_kernel(const _Float16 *__restric
     // activation copy, global memory straight into LDS (no register hop): the i-th load of a wavefront
     // fills the 64 consecutive 16-byte slots from 64*wave + 256*i, lane by lane; slot (row, pos) holds
     // chunk pos ^ (row & 15) of its row, so each lane fetches that chunk.  Rows past M re-read row M-1.
+    // Source addresses are the group's byte offset in a row (uniform) plus a 32-bit lane offset.
     const int xrow = 4 * wave + (lane >> 4), xch = (lane & 15) ^ (xrow & 15);
-    const _Float16 *xsrc[8];
+    uint32_t xoff[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i)
-        xsrc[i] = x + (size_t)min(m0 + xrow + 16 * i, M - 1) * K + xch * 8;
+        xoff[i] = ((uint32_t)min(m0 + xrow + 16 * i, M - 1) * (uint32_t)K + (uint32_t)xch * 8u) * 2u;
+    GemmBuffers buf;
+    buf.x = make_rsrc(x, (uint32_t)M * (uint32_t)K * 2u);
+    if constexpr (BITS == DENSE) {
+        buf.packed = make_rsrc(packed, (uint32_t)N * (uint32_t)K * 2u);
+        buf.scales = buf.zeros = buf.packed; // unused
+    } else {
+        const uint32_t Np = (uint32_t)(N + 63) / 64u * 64u;
+        buf.packed = make_rsrc(packed, Np / 8u * (uint32_t)K * (uint32_t)BITS);
+        buf.scales = make_rsrc(scales, Np * (uint32_t)G * 2u);
+        buf.zeros = make_rsrc(zeros, Np * (uint32_t)G * 2u);
+    }
 
     f4 acc[QNB][QMB];
 #pragma unroll
@@ -118,10 +131,10 @@ __global__ __launch_bounds__(256, 2) void qgemm_kernel(const _Float16 *__restric
     WChunk<BITS> wc[QNB];
 #pragma unroll
     for (int i = 0; i < 8; ++i)
-        __builtin_amdgcn_global_load_lds(xsrc[i], &Xs[0][64 * wave + 256 * i], 16, 0, 0);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(buf.x, &Xs[0][64 * wave + 256 * i], 16, xoff[i], 0, 0, 0);
 #pragma unroll
     for (int i = 0; i < QNB; ++i)
-        load_wchunk<BITS>(wc[i], packed, scales, zeros, rb0 + i, Np16, G, 0, lane);
+        load_wchunk<BITS>(wc[i], buf, rb0 + i, Np16, G, K, 0, lane);
     __builtin_amdgcn_s_waitcnt(FQ_WAIT_VMCNT0); // the copies into LDS have landed ...
     __syncthreads();                            // ... in every wavefront
 
@@ -138,7 +151,7 @@ __global__ __launch_bounds__(256, 2) void qgemm_kernel(const _Float16 *__restric
             } else {
                 h2 q[16];
                 unpack_codes<BITS>(wc[i].c, q);
-                const h2 z2 = {wc[i].zero, wc[i].zero}, s2 = {wc[i].scale, wc[i].scale};
+                const h2 z2 = as_h2(wc[i].zero * 0x10001u), s2 = as_h2(wc[i].scale * 0x10001u); // both halves
 #pragma unroll
                 for (int p = 0; p < 16; ++p)
                     q[p] = (q[p] - z2) * s2;
@@ -152,11 +165,11 @@ __global__ __launch_bounds__(256, 2) void qgemm_kernel(const _Float16 *__restric
         if (more) {
 #pragma unroll
             for (int i = 0; i < 8; ++i)
-                __builtin_amdgcn_global_load_lds(xsrc[i] + (size_t)(g + 1) * 128, &Xs[cur ^ 1][64 * wave + 256 * i], 16,
-                                                 0, 0);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(buf.x, &Xs[cur ^ 1][64 * wave + 256 * i], 16, xoff[i],
+                                                         (uint32_t)(g + 1) * 256u, 0, 0);
 #pragma unroll
             for (int i = 0; i < QNB; ++i)
-                load_wchunk<BITS>(wc[i], packed, scales, zeros, rb0 + i, Np16, G, g + 1, lane);
+                load_wchunk<BITS>(wc[i], buf, rb0 + i, Np16, G, K, g + 1, lane);
         }
         // contraction
 #pragma unroll
@@ -232,8 +245,14 @@ int launch_q(const void *x, int M, const fq_packed_ref &w, void *out, fq_stream 
 
 } // namespace
 
+// The kernels address x, the packed weights and the scales/zeros through 32-bit byte offsets.
+static bool fits_32bit(size_t a, size_t b, size_t elem_bytes) { return a * b * elem_bytes < ((size_t)1 << 32); }
+
 int fq_launch_gemm(const void *x, int M, const fq_packed_ref &w, void *out, fq_stream st)
 {
+    const size_t Np = ((size_t)w.N + 63) / 64 * 64;
+    if (!fits_32bit(M, w.K, 2) || Np / 8 * w.K * w.bits >= ((size_t)1 << 32))
+        return (int)hipErrorInvalidValue;
     switch (w.bits) {
     case 2: return launch_q<2>(x, M, w, out, st);
     case 3: return launch_q<3>(x, M, w, out, st);
@@ -244,5 +263,7 @@ int fq_launch_gemm(const void *x, int M, const fq_packed_ref &w, void *out, fq_s
 
 int fq_launch_dense(const void *x, int M, const void *W, int N, int K, void *out, fq_stream st)
 {
+    if (!fits_32bit(M, K, 2) || !fits_32bit(N, K, 2))
+        return (int)hipErrorInvalidValue;
     return launch_tile<DENSE, 2>(x, M, W, nullptr, nullptr, N, K, out, st);
 }
