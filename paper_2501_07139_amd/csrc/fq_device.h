@@ -218,6 +218,119 @@ __device__ __forceinline__ void unpack_codes(const uint32_t (&C)[BITS], h2 (&q)[
     }
 }
 
+// ---------------------------------------------------------------------------
+// Unpack for the matrix-core GEMM: (code - zero) * scale per weight, in packed fp16.
+// A code field at bit p of a half's mantissa, OR-ed with the exponent of 2^(10-p), reads 2^(10-p) + code:
+// the code itself, not code * 2^p.  Taking the bias away is then an exact addition, and when the zero is
+// an integer (what the quantizer produces) bias and zero leave together in one addition:
+//     q = (biased + (-(2^(10-p)) - zero)) * scale          3 operations per pair with the and-or
+// The sum is exact because bias + zero is an integer below 2048.  With fractional zeros (zeros rescaled
+// after truncating code bits) the two additions are taken separately.
+// ---------------------------------------------------------------------------
+template <int P>
+__device__ __forceinline__ uint32_t exp_for_shift()
+{
+    uint32_t e = (uint32_t)((25 - P) << 10) * 0x10001u; // exponent field of 2^(10-P), both halves
+    asm volatile("" : "+v"(e));                          // vector register: see exp1024_reg()
+    return e;
+}
+
+template <int P>
+__device__ __forceinline__ h2 minus_bias()
+{
+    constexpr float b = -(float)(1 << (10 - P));
+    return h2{(_Float16)b, (_Float16)b};
+}
+
+// pairs of one k-step: which shift each uses (index into the per-shift constants) and how to extract it
+template <int BITS>
+struct UnpackPlan;
+template <>
+struct UnpackPlan<4> { static constexpr int NSHIFT = 2; };
+template <>
+struct UnpackPlan<2> { static constexpr int NSHIFT = 5; };
+template <>
+struct UnpackPlan<3> { static constexpr int NSHIFT = 3; };
+template <>
+struct UnpackPlan<8> { static constexpr int NSHIFT = 1; };
+
+// INTZ: the caller has made sure that the zero is an integer.
+template <int BITS, bool INTZ>
+__device__ __forceinline__ void unpack_dequant(const uint32_t (&C)[BITS], h2 zero2, h2 scale2, h2 (&q)[16])
+{
+    constexpr int NS = UnpackPlan<BITS>::NSHIFT;
+    uint32_t b[16]; // biased pairs
+    int sh[16];     // index of the shift of each pair (compile-time after unrolling)
+    h2 mb[NS];      // -2^(10-p) per shift
+    if constexpr (BITS == 4) {
+        const uint32_t E0 = exp_for_shift<0>(), E4 = exp_for_shift<4>();
+        mb[0] = minus_bias<0>(); mb[1] = minus_bias<4>();
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const uint32_t w = C[s], t = w >> 8;
+            b[4 * s + 0] = (w & 0x000f000fu) | E0; sh[4 * s + 0] = 0;
+            b[4 * s + 1] = (w & 0x00f000f0u) | E4; sh[4 * s + 1] = 1;
+            b[4 * s + 2] = (t & 0x000f000fu) | E0; sh[4 * s + 2] = 0;
+            b[4 * s + 3] = (t & 0x00f000f0u) | E4; sh[4 * s + 3] = 1;
+        }
+    } else if constexpr (BITS == 2) {
+        const uint32_t E0 = exp_for_shift<0>(), E2 = exp_for_shift<2>(), E4 = exp_for_shift<4>(),
+                       E6 = exp_for_shift<6>(), E8 = exp_for_shift<8>();
+        mb[0] = minus_bias<0>(); mb[1] = minus_bias<2>(); mb[2] = minus_bias<4>(); mb[3] = minus_bias<6>();
+        mb[4] = minus_bias<8>();
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const uint32_t w = C[j], t = w >> 10;
+            b[8 * j + 0] = (w & 0x00030003u) | E0; sh[8 * j + 0] = 0;
+            b[8 * j + 1] = (w & 0x000c000cu) | E2; sh[8 * j + 1] = 1;
+            b[8 * j + 2] = (w & 0x00300030u) | E4; sh[8 * j + 2] = 2;
+            b[8 * j + 3] = (w & 0x00c000c0u) | E6; sh[8 * j + 3] = 3;
+            b[8 * j + 4] = (w & 0x03000300u) | E8; sh[8 * j + 4] = 4;
+            b[8 * j + 5] = (t & 0x00030003u) | E0; sh[8 * j + 5] = 0;
+            b[8 * j + 6] = (t & 0x000c000cu) | E2; sh[8 * j + 6] = 1;
+            b[8 * j + 7] = (t & 0x00300030u) | E4; sh[8 * j + 7] = 2;
+        }
+    } else if constexpr (BITS == 8) {
+        const uint32_t E0 = exp_for_shift<0>();
+        mb[0] = minus_bias<0>();
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const uint32_t w = C[j];
+            b[2 * j + 0] = (w & 0x00ff00ffu) | E0; sh[2 * j + 0] = 0;
+            b[2 * j + 1] = ((w >> 8) & 0x00ff00ffu) | E0; sh[2 * j + 1] = 0;
+        }
+    } else {
+        const uint32_t E0 = exp_for_shift<0>(), E3 = exp_for_shift<3>(), E6 = exp_for_shift<6>();
+        mb[0] = minus_bias<0>(); mb[1] = minus_bias<3>(); mb[2] = minus_bias<6>();
+#pragma unroll
+        for (int d = 0; d < 3; ++d) {
+            const uint32_t w = C[d], t = w >> 9;
+            b[5 * d + 0] = (w & 0x00070007u) | E0; sh[5 * d + 0] = 0;
+            b[5 * d + 1] = (w & 0x00380038u) | E3; sh[5 * d + 1] = 1;
+            b[5 * d + 2] = (w & 0x01c001c0u) | E6; sh[5 * d + 2] = 2;
+            b[5 * d + 3] = (t & 0x00070007u) | E0; sh[5 * d + 3] = 0;
+            b[5 * d + 4] = (t & 0x00380038u) | E3; sh[5 * d + 4] = 1;
+        }
+        uint32_t sp = ((C[0] >> 15) & 0x00010001u) | E0;
+        sp |= (C[1] >> 14) & 0x00020002u;
+        sp |= (C[2] >> 13) & 0x00040004u;
+        b[15] = sp; sh[15] = 0;
+    }
+    if constexpr (INTZ) {
+        h2 mbz[NS];
+#pragma unroll
+        for (int i = 0; i < NS; ++i)
+            mbz[i] = mb[i] - zero2; // exact: an integer below 2048
+#pragma unroll
+        for (int p = 0; p < 16; ++p)
+            q[p] = (as_h2(b[p]) + mbz[sh[p]]) * scale2;
+    } else {
+#pragma unroll
+        for (int p = 0; p < 16; ++p)
+            q[p] = ((as_h2(b[p]) + mb[sh[p]]) - zero2) * scale2;
+    }
+}
+
 // Biased pairs without the fix-up: h[4*s + v] reads, as two fp16 numbers,
 // 1024 + code * 2^pair_shift(4*s + v) for elements 2v and 2v+1 of k-step s.  The
 // streaming kernel feeds these to the matrix core as they are and removes the

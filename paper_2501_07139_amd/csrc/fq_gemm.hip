@@ -23,6 +23,8 @@
 #include "fq_device.h"
 #include "fq_internal.h"
 
+#include <type_traits>
+
 namespace {
 
 // ------------------------------------------------------------ quantized GEMM
@@ -138,6 +140,23 @@ __global__ __launch_bounds__(256, 2) void qgemm_kernel(const _Float16 *__restric
     __builtin_amdgcn_s_waitcnt(FQ_WAIT_VMCNT0); // the copies into LDS have landed ...
     __syncthreads();                            // ... in every wavefront
 
+    // Integer zeros (what the quantizer produces) let bias and zero leave a pair in one addition: look
+    // at the zeros of this workgroup's weight rows once and take the matching copy of the main loop.
+    bool intz = true;
+    if constexpr (BITS != DENSE && QNB != 4) {
+        const uint32_t first = (uint32_t)(n0 >> 4) * (uint32_t)G * 16u, count = (QBN / 16) * (uint32_t)G * 16u;
+        int frac = 0;
+        for (uint32_t i = (uint32_t)tid * 8u; i < count; i += 256u * 8u) { // past the array: zeros
+            const h8 z = __builtin_bit_cast(h8, buf_load_b128(buf.zeros, (first + i) * 2u, 0));
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                frac |= z[e] != __builtin_truncf16(z[e]);
+        }
+        intz = !__syncthreads_or(frac);
+    }
+
+    auto main_loop = [&](auto intz_tag) {
+    constexpr bool INTZ = decltype(intz_tag)::value;
     for (int g = 0; g < G; ++g) {
         const int cur = g & 1;
         // dequantize this group's weights into operands: (code - zero) * scale
@@ -150,11 +169,7 @@ __global__ __launch_bounds__(256, 2) void qgemm_kernel(const _Float16 *__restric
                     a[i][s] = wc[i].f[s];
             } else {
                 h2 q[16];
-                unpack_codes<BITS>(wc[i].c, q);
-                const h2 z2 = as_h2(wc[i].zero * 0x10001u), s2 = as_h2(wc[i].scale * 0x10001u); // both halves
-#pragma unroll
-                for (int p = 0; p < 16; ++p)
-                    q[p] = (q[p] - z2) * s2;
+                unpack_dequant<BITS, INTZ>(wc[i].c, as_h2(wc[i].zero * 0x10001u), as_h2(wc[i].scale * 0x10001u), q);
 #pragma unroll
                 for (int s = 0; s < 4; ++s)
                     a[i][s] = make_h8(q[4 * s], q[4 * s + 1], q[4 * s + 2], q[4 * s + 3]);
@@ -189,6 +204,13 @@ __global__ __launch_bounds__(256, 2) void qgemm_kernel(const _Float16 *__restric
         __builtin_amdgcn_s_waitcnt(FQ_WAIT_VMCNT0);
         __syncthreads();
     }
+    };
+    if constexpr (QNB == 4)
+        main_loop(std::false_type{}); // the wide tile has no registers to spare for a second copy of the loop
+    else if (intz)
+        main_loop(std::true_type{});
+    else
+        main_loop(std::false_type{});
 
     // store: lane holds m = lane%16 and n = 4*(lane/16) + v of each 16x16 block
 #pragma unroll
