@@ -240,23 +240,90 @@ struct GemvCursor {
 template <int MODE>
 struct GemvInputs { static constexpr int N = MODE == 2 ? 3 : (MODE >= 3 ? 2 : 1); };
 
-// One chunk of the block's tensor that feeds the last rms, in fp32.
+// One chunk (8 consecutive k) of the block's tensor that feeds the last rms.  Where that tensor is an
+// fp16 one (modes 0, 1 and 3: a stored activation, or the stored sum of two) it stays in packed fp16: the
+// packed add rounds a + b once, like the fp32 add followed by a conversion, since the fp32 sum of two
+// fp16 numbers is exact or already beyond fp16's precision.  Otherwise it is held in fp32.
 template <int MODE>
-__device__ __forceinline__ void gemv_combine(const h8 (&r)[GemvInputs<MODE>::N], float (&v)[8])
+struct GemvChunk {
+    static constexpr bool HALF = MODE == 0 || MODE == 1 || MODE == 3;
+    h8 h;       // HALF
+    float f[8]; // !HALF
+};
+
+template <int MODE>
+__device__ __forceinline__ void gemv_combine(const h8 (&r)[GemvInputs<MODE>::N], GemvChunk<MODE> &v)
+{
+    if constexpr (MODE == 0 || MODE == 1) {
+        v.h = r[0];
+    } else if constexpr (MODE == 3) {
+        v.h = r[0] + r[1];
+    } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            float t = (float)r[0][e];
+            if constexpr (MODE == 2)
+                t = t + (float)r[1][e] + (float)r[2][e];
+            else if constexpr (MODE == 4)
+                t = t * __builtin_amdgcn_rcpf(1.0f + __expf(-t)) * (float)r[1][e]; // reciprocal good to 1 ulp
+            else
+                t = t + (float)r[1][e];
+            v.f[e] = t;
+        }
+    }
+}
+
+// sum of the squares / of the elements of a packed chunk, accumulated in fp32 (two products per instruction)
+__device__ __forceinline__ float gemv_sumsq(h8 v, float acc)
 {
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        float t = (float)r[0][e];
-        if constexpr (MODE == 2)
-            t = t + (float)r[1][e] + (float)r[2][e];
-        else if constexpr (MODE == 3)
-            t = (float)(_Float16)(t + (float)r[1][e]); // the sum is a stored fp16 tensor
-        else if constexpr (MODE == 4)
-            t = t * __builtin_amdgcn_rcpf(1.0f + __expf(-t)) * (float)r[1][e]; // reciprocal good to 1 ulp
-        else if constexpr (MODE == 5)
-            t = t + (float)r[1][e];
-        v[e] = t;
+    for (int i = 0; i < 4; ++i) {
+        const h2 p = {v[2 * i], v[2 * i + 1]};
+        acc = __builtin_amdgcn_fdot2(p, p, acc, false);
     }
+    return acc;
+}
+
+__device__ __forceinline__ float gemv_sum(h8 v)
+{
+    const h2 one = {(_Float16)1.0f, (_Float16)1.0f};
+    float acc = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const h2 p = {v[2 * i], v[2 * i + 1]};
+        acc = __builtin_amdgcn_fdot2(p, one, acc, false);
+    }
+    return acc;
+}
+
+// v * scale in fp32, rounded to fp16
+__device__ __forceinline__ h8 gemv_scaled(const float (&v)[8], float scale)
+{
+    h8 r;
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+        r[e] = (_Float16)(v[e] * scale);
+    return r;
+}
+
+__device__ __forceinline__ h8 gemv_scaled(h8 v, float scale)
+{
+    h8 r;
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+        r[e] = (_Float16)((float)v[e] * scale);
+    return r;
+}
+
+// 2^-pair_shift of the eight elements of k-step s, as a packed constant
+template <int BITS>
+__device__ __forceinline__ h8 stage_factors(int s)
+{
+    h8 f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+        f[e] = (_Float16)stage_factor<BITS>(s, e);
+    return f;
 }
 
 // s_waitcnt immediate: vector-memory loads in flight <= n (n < 64), the other counters left alone
@@ -375,7 +442,8 @@ __device__ __forceinline__ void gemv_body(const GemvJob job, int bj, const GemvI
     // its own.  Chunk kc of row mm (8 halves at k = 8*kc) goes to xl[kc*M + mm], divided by 2^p.
     // MODE 4 (the expensive transform) is evaluated once: the first pass over the row leaves the eight
     // fp32 products in the two 16-byte slots of its inputs, which only this thread touches.
-    auto fetch = [&](int t, float (&v)[8], bool first) { // this thread's chunk of trip t, combined
+    using Chunk = GemvChunk<MODE>;
+    auto fetch = [&](int t, Chunk &v, bool first) { // this thread's chunk of trip t, combined
         h8 r[NIN];
 #pragma unroll
         for (int i = 0; i < NIN; ++i)
@@ -384,15 +452,15 @@ __device__ __forceinline__ void gemv_body(const GemvJob job, int bj, const GemvI
             if (first) {
                 gemv_combine<MODE>(r, v);
                 if (t > 0) { // trip 0 stays in registers
-                    raw[t * STEP + tid] = __builtin_bit_cast(h8, f4{v[0], v[1], v[2], v[3]});
-                    raw[(trips + t) * STEP + tid] = __builtin_bit_cast(h8, f4{v[4], v[5], v[6], v[7]});
+                    raw[t * STEP + tid] = __builtin_bit_cast(h8, f4{v.f[0], v.f[1], v.f[2], v.f[3]});
+                    raw[(trips + t) * STEP + tid] = __builtin_bit_cast(h8, f4{v.f[4], v.f[5], v.f[6], v.f[7]});
                 }
             } else {
                 const f4 lo = __builtin_bit_cast(f4, r[0]), hi = __builtin_bit_cast(f4, r[1]);
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    v[e] = lo[e];
-                    v[4 + e] = hi[e];
+                    v.f[e] = lo[e];
+                    v.f[4 + e] = hi[e];
                 }
             }
         } else {
@@ -403,7 +471,7 @@ __device__ __forceinline__ void gemv_body(const GemvJob job, int bj, const GemvI
     // to K = 4096); later trips are fetched from LDS again.
     int sums = 0; // block sums taken so far: selects the partials' buffer
     auto stage_row = [&](int mm) {
-        float v0[8];
+        Chunk v0;
         const bool has0 = tid < chunks;
         if (has0)
             fetch(0, v0, true);
@@ -412,18 +480,22 @@ __device__ __forceinline__ void gemv_body(const GemvJob job, int bj, const GemvI
             // sum of squares of the row; second: of the fp16 result of the first rms
             auto squares = [&](bool second) {
                 float ss = 0.f;
-                auto add = [&](const float (&v)[8]) {
+                auto add = [&](const Chunk &v) {
+                    if constexpr (Chunk::HALF) {
+                        ss = gemv_sumsq(v.h, ss);
+                    } else if (second) {
+                        ss = gemv_sumsq(gemv_scaled(v.f, inv1), ss);
+                    } else {
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        const float y = second ? (float)(_Float16)(v[e] * inv1) : v[e];
-                        ss += y * y;
+                        for (int e = 0; e < 8; ++e)
+                            ss = fmaf(v.f[e], v.f[e], ss);
                     }
                 };
                 if (has0)
                     add(v0);
                 for (int t = 1; t < trips; ++t)
                     if (tid + STEP * t < chunks) {
-                        float v[8];
+                        Chunk v;
                         fetch(t, v, !second);
                         add(v);
                     }
@@ -435,35 +507,27 @@ __device__ __forceinline__ void gemv_body(const GemvJob job, int bj, const GemvI
         }
         // writes one chunk of x to LDS, and the group sums (the 16 lanes that share a group are all here:
         // chunks is a multiple of 16)
-        auto put = [&](int kc, float (&v)[8]) {
-            if constexpr (MODE == 5) {
-#pragma unroll
-                for (int e = 0; e < 8; ++e)
-                    v[e] = (float)(_Float16)(v[e] * inv1);
-            }
-            if constexpr (MODE == 3 || MODE == 5) {
-                if (blockIdx.x == 0) {
-                    h8 o;
-#pragma unroll
-                    for (int e = 0; e < 8; ++e)
-                        o[e] = (_Float16)v[e]; // exact: already fp16 values
-                    *reinterpret_cast<h8 *>(in.aux + (size_t)mm * K + (size_t)kc * 8) = o;
+        auto put = [&](int kc, const Chunk &v) {
+            h8 xe; // the linear's input, fp16
+            if constexpr (MODE == 0) {
+                xe = v.h;
+            } else if constexpr (MODE == 5) {
+                const h8 y = gemv_scaled(v.f, inv1); // the stored block output
+                if (blockIdx.x == 0)
+                    *reinterpret_cast<h8 *>(in.aux + (size_t)mm * K + (size_t)kc * 8) = y;
+                xe = gemv_scaled(y, inv2);
+            } else if constexpr (Chunk::HALF) {
+                if constexpr (MODE == 3) {
+                    if (blockIdx.x == 0)
+                        *reinterpret_cast<h8 *>(in.aux + (size_t)mm * K + (size_t)kc * 8) = v.h;
                 }
+                xe = gemv_scaled(v.h, inv1);
+            } else {
+                xe = gemv_scaled(v.f, inv1);
             }
-            const float inv = MODE == 5 ? inv2 : inv1;
-            const int s = (kc >> 2) & 3;
-            h8 w;
-            float sx = 0.f, sc = 0.f;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const float xe = MODE == 0 ? v[e] : (float)(_Float16)(v[e] * inv);
-                w[e] = (_Float16)(xe * stage_factor<BITS>(s, e));
-                sx += xe;
-                sc += (float)w[e];
-            }
+            const h8 w = xe * stage_factors<BITS>((kc >> 2) & 3); // exact: powers of two
             xl[(size_t)kc * M + mm] = w;
-            sx = row16_sum(sx);
-            sc = row16_sum(sc);
+            const float sx = row16_sum(gemv_sum(xe)), sc = row16_sum(gemv_sum(w));
             if ((kc & 15) == 0) {
                 xsum[(kc >> 4) * 16 + mm] = sx;
                 csum[(kc >> 4) * 16 + mm] = 1024.0f * sc;
@@ -473,7 +537,7 @@ __device__ __forceinline__ void gemv_body(const GemvJob job, int bj, const GemvI
             put(tid, v0);
         for (int t = 1; t < trips; ++t)
             if (tid + STEP * t < chunks) {
-                float v[8];
+                Chunk v;
                 fetch(t, v, false);
                 put(tid + STEP * t, v);
             }

@@ -87,7 +87,8 @@ def test_dequant_arbitrary_codes_and_fractional_zeros(fq, torch, bits):
 
 
 # ------------------------------------------------------------------- qlinear
-GEMV_CASES = [(1, 512, 512), (16, 512, 512), (3, 200, 384), (1, 4096, 4096), (5, 70, 256), (1, 1, 128)]
+GEMV_CASES = [(1, 512, 512), (16, 512, 512), (3, 200, 384), (1, 4096, 4096), (5, 70, 256), (1, 1, 128),
+              (1, 160, 11008), (3, 96, 11008)]  # rows longer than one pass of the staging
 GEMM_CASES = [(17, 512, 512), (64, 512, 512), (300, 200, 384), (520, 384, 1024), (33, 70, 256), (256, 64, 128)]
 
 
@@ -286,6 +287,30 @@ def test_stack_forward_against_oracle(fq, torch, M):
         assert np.max(np.abs(gout.astype(np.float64) - t["x_next"].astype(np.float64))) <= 1e-2, l
         xin = gout
     assert np.array_equal(xin.view(np.uint16), got.view(np.uint16))
+
+
+@pytest.mark.parametrize("M", [1, 40])
+def test_stack_forward_replays_from_a_captured_graph(fq, torch, M):
+    """The launches of a stack forward can be captured once and replayed: every replay, with eager work
+    and synchronisations in between, gives the eager result bit for bit."""
+    stack, host, sh = build_stack(fq, "tiny", 320)
+    bitvec = fq_synth.bit_vector(7, 7 * sh["layers"], probs=(0.25, 0.25, 0.25, 0.25))
+    x = dev(torch, fq_synth.activations(321, M, sh["hidden"]))
+    ws = torch.empty(fq.fq_stack_workspace_bytes(M, sh["hidden"], sh["ffn"]), dtype=torch.uint8, device="cuda")
+    out = torch.empty_like(x)
+    fq.fq_stack_forward(stack, bitvec, x, out=out, workspace=ws)  # eager; also the warm-up before capture
+    torch.cuda.synchronize()
+    want = out.clone()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        fq.fq_stack_forward(stack, bitvec, x, out=out, workspace=ws)
+    for r in range(4):
+        out.fill_(float("nan"))
+        ws.random_(0, 255)  # eager work between the replays; the workspace holds no state
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out.view(torch.int16), want.view(torch.int16)), r
 
 
 def test_block_steps_teacher_forced(fq, torch):

@@ -108,6 +108,10 @@ def test_error_codes_without_launching_anything():
     assert lib.fq_token_nll(None, None, 1, 1, None, None) == -1
     assert lib.fq_glue(9, 16, 16, 16, 1, 128, 16, None) == -2
     assert lib.fq_dense_f16(16, 1, 16, 1, 100, 16, None) == -2
+    # the matrix-core kernels address their arrays through 32-bit offsets: 4 GiB of activations is refused
+    assert lib.fq_qlinear(16, 1 << 20, 16, 16, 16, 128, 4096, 4, 128, 16, None) == -2
+    assert "4 GiB" in fq.fq_last_error()
+    assert lib.fq_dense_f16(16, 1 << 20, 16, 128, 4096, 16, None) == -2
     assert fq.fq_stack_workspace_bytes(0, 128, 128) == 0
 
 
