@@ -231,6 +231,18 @@ def token_nll(logits, labels) -> np.ndarray:
     return out
 
 
+def logit_l2(a, b) -> np.ndarray:
+    """Row-wise Euclidean distance between two fp16 logit arrays [M,V] (the sensitivity value of the
+    search's analysis filter is this distance between a hybrid model's logits and QM(n_up)'s)."""
+    a = _c(np.asarray(a).view(np.uint16), np.uint16)
+    b = _c(np.asarray(b).view(np.uint16), np.uint16)
+    assert a.shape == b.shape and a.ndim == 2
+    M, V = a.shape
+    out = np.empty(M, dtype=np.float64)
+    _check(_load().ora_logit_l2(_p(a), _p(b), M, V, _p(out)), "logit_l2")
+    return out
+
+
 def perplexity(nll) -> float:
     """exp(mean token NLL) of one sequence."""
     return float(np.exp(np.mean(np.asarray(nll, dtype=np.float64))))

@@ -399,3 +399,28 @@ int ora_token_nll(const uint16_t *logits, const int32_t *labels, int M, int V, d
     }
     return 0;
 }
+
+/*
+ * Euclidean distance between two sets of fp16 logits, row by row (Section
+ * "Search method": the sensitivity value of a module is the Euclidean distance
+ * between the logits of the hybrid model and those of QM(n_up)):
+ *   dist[m] = sqrt(sum_v (a[m,v] - b[m,v])^2)
+ * The distance over a whole batch of rows is sqrt(sum_m dist[m]^2).
+ */
+int ora_logit_l2(const uint16_t *a, const uint16_t *b, int M, int V, double *dist)
+{
+    if (!a || !b || !dist)
+        return -1;
+#pragma omp parallel for schedule(static)
+    for (int m = 0; m < M; ++m) {
+        const uint16_t *ra = a + (size_t)m * V, *rb = b + (size_t)m * V;
+        double ss = 0.0;
+        for (int v = 0; v < V; ++v) {
+            const double d = ora_h2d(ra[v]) - ora_h2d(rb[v]);
+            ss += d * d;
+        }
+        dist[m] = sqrt(ss);
+    }
+    return 0;
+}
+

@@ -426,6 +426,41 @@ def test_token_nll_against_float64_logsumexp_and_perplexity():
     assert abs(oracle.perplexity(got) - math.exp(want.mean())) < 1e-9 * math.exp(want.mean())
 
 
+# ------------------------------------------------------------- logit distance
+def test_logit_l2_closed_forms_and_metric_properties():
+    V = 1000
+    a = fq_synth.logits(30, 6, V)
+    # identical logits: distance 0; a single changed entry: its absolute change
+    assert np.all(oracle.logit_l2(a, a) == 0.0)
+    b = a.copy()
+    b[2, 17] = np.float16(float(a[2, 17]) + 3.0)
+    d = oracle.logit_l2(a, b)
+    want = abs(float(b[2, 17]) - float(a[2, 17]))
+    assert d[2] == want and np.all(np.delete(d, 2) == 0.0)
+    # a 3-4-5 triangle spread over two entries, and k equal offsets: |c| sqrt(k)
+    z = np.zeros((2, V), dtype=np.float16)
+    y = z.copy()
+    y[0, 5], y[0, 900] = 3.0, -4.0
+    y[1, :64] = 0.5
+    got = oracle.logit_l2(y, z)
+    assert got[0] == 5.0 and got[1] == 0.5 * 8.0
+    # symmetry, and the triangle inequality against a third point
+    c = fq_synth.logits(31, 6, V)
+    e = fq_synth.logits(32, 6, V)
+    dac, dca = oracle.logit_l2(a, c), oracle.logit_l2(c, a)
+    assert np.array_equal(dac, dca)
+    assert np.all(dac <= oracle.logit_l2(a, e) + oracle.logit_l2(e, c) + 1e-12)
+    # brute force in Python floats on a tiny case
+    small_a, small_c = a[:2, :7], c[:2, :7]
+    for m in range(2):
+        ss = 0.0
+        for v in range(7):
+            ss += (float(small_a[m, v]) - float(small_c[m, v])) ** 2
+        assert abs(oracle.logit_l2(small_a, small_c)[m] - math.sqrt(ss)) < 1e-13
+    # independent N(0, s^2) logits: distance ~ s sqrt(2V)
+    assert np.all(np.abs(dac / (1.28 * math.sqrt(2 * V)) - 1) < 0.1)
+
+
 # ------------------------------------------------------------- paper arithmetic
 def test_numbers_the_paper_prints():
     vals = {}
