@@ -190,6 +190,10 @@ def main():
     ms_head = timed(lambda: fq.fq_dense_f16(h_out, head, out=logits), reps)
     ms_nll = timed(lambda: fq.fq_token_nll(logits, labels, out=nll), reps)
     ms_dec = timed(leg_b, reps)
+    # beyond the step: the logit distance of the search's sensitivity analysis (reads two logit arrays once)
+    logits_b = torch.empty_like(logits).normal_(0.0, 1.28)
+    l2 = torch.empty(M_FWD, dtype=torch.float32, device=dev)
+    ms_l2 = timed(lambda: fq.fq_logit_l2(logits, logits_b, out=l2), reps)
 
     # the dominant kernel: dequant-GEMM launches of leg A, one by one
     kernels = []
@@ -258,6 +262,8 @@ def main():
                            "ms_block_forward": round(ms_fwd_block, 4), "frac_mfma_peak": round(gemm_tflops / PEAK_MFMA_F16_TFLOPS, 4)},
             "head_m2048": {"tflops": round(head_flops / ms_head / 1e9, 1), "ms": round(ms_head, 4)},
             "nll": {"GBps": round(nll_bytes / ms_nll / 1e6, 1), "ms": round(ms_nll, 4)},
+            "logit_l2_outside_the_step": {"GBps": round(2 * nll_bytes / ms_l2 / 1e6, 1), "ms": round(ms_l2, 4),
+                                          "frac_hbm_peak": round(2 * nll_bytes / ms_l2 / 1e6 / PEAK_HBM_GBPS, 4)},
             "gemv_m1": {"GBps_single_launches": round(block_bytes / gemv_ms_total / 1e6, 1),
                         "GBps_stack_decode": round(gemv_bytes / ms_dec / 1e6, 1),
                         "ms_stack_decode": round(ms_dec, 4), "layers": DECODE_LAYERS,

@@ -188,6 +188,17 @@ int fq_dense_f16(const void *x, int M, const void *W, int N, int K, void *out, v
  */
 int fq_token_nll(const void *logits, const int32_t *labels, int M, int V, float *nll_out, void *stream);
 
+/*
+ * Row-wise Euclidean distance between two sets of logits (Section "Search
+ * method": the sensitivity value of a module is the Euclidean distance between
+ * the logits of the hybrid model with that module lowered and those of
+ * QM(n_up)):  dist[m] = sqrt(sum_v (a[m,v] - b[m,v])^2), differences, squares
+ * and the sum in fp32.  a, b fp16 [M,V] row-major: device, read, 16-byte
+ * aligned.  dist fp32 [M]: device, written.  The distance over a batch of rows
+ * is sqrt(sum_m dist[m]^2).  One pass over both arrays.
+ */
+int fq_logit_l2(const void *a, const void *b, int M, int V, float *dist_out, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

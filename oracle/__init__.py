@@ -234,8 +234,11 @@ def token_nll(logits, labels) -> np.ndarray:
 def logit_l2(a, b) -> np.ndarray:
     """Row-wise Euclidean distance between two fp16 logit arrays [M,V] (the sensitivity value of the
     search's analysis filter is this distance between a hybrid model's logits and QM(n_up)'s)."""
-    a = _c(np.asarray(a).view(np.uint16), np.uint16)
-    b = _c(np.asarray(b).view(np.uint16), np.uint16)
+    a, b = np.asarray(a), np.asarray(b)
+    if a.dtype != np.float16 or b.dtype != np.float16:
+        raise TypeError("logit_l2 takes fp16 logits (round fp64 ones with round_f16 first)")
+    a = _c(a.view(np.uint16), np.uint16)
+    b = _c(b.view(np.uint16), np.uint16)
     assert a.shape == b.shape and a.ndim == 2
     M, V = a.shape
     out = np.empty(M, dtype=np.float64)

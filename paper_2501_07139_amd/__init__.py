@@ -42,7 +42,7 @@ class fq_layer(ctypes.Structure):
 
 def _load() -> ctypes.CDLL:
     if not os.path.exists(LIB_PATH):
-        raise ImportError(f"{LIB_PATH} is not built; run `python -m paper_2501_07139_amd.build`")
+        raise ImportError(f"{LIB_PATH} is not built; run `python paper_2501_07139_amd/build.py`")
     # PyTorch ships its own HIP runtime (same soname).  Import it first so that libfq binds to
     # that one copy; two runtimes in one process do not both see the device.
     import torch  # noqa: F401
@@ -63,6 +63,7 @@ def _load() -> ctypes.CDLL:
         "fq_glue": (ci, [ci, vp, vp, vp, ci, ci, vp, vp]),
         "fq_dense_f16": (ci, [vp, ci, vp, ci, ci, vp, vp]),
         "fq_token_nll": (ci, [vp, vp, ci, ci, vp, vp]),
+        "fq_logit_l2": (ci, [vp, vp, ci, ci, vp, vp]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -74,7 +75,7 @@ def _load() -> ctypes.CDLL:
 _lib = _load()
 EXPORTS = ("fq_last_error", "fq_version", "fq_quantize_rtn", "fq_packed_bytes", "fq_meta_count", "fq_pack_groups",
            "fq_dequant", "fq_qlinear", "fq_stack_workspace_bytes", "fq_stack_forward", "fq_glue", "fq_dense_f16",
-           "fq_token_nll")
+           "fq_token_nll", "fq_logit_l2")
 
 
 def _check(rc: int) -> None:
@@ -272,6 +273,19 @@ def fq_dense_f16(x, W, out=None, stream=None):
     if out is None:
         out = torch.empty((M, N), dtype=torch.float16, device=x.device)
     _check(_lib.fq_dense_f16(_dp(x), M, _dp(W), N, K, _dp(out), _stream(stream)))
+    return out
+
+
+def fq_logit_l2(a, b, out=None, stream=None):
+    torch = _torch()
+    a = _dev(a, torch.float16, "a")
+    b = _dev(b, torch.float16, "b")
+    if a.shape != b.shape or a.dim() != 2:
+        raise ValueError("fq_logit_l2: a and b must be [M,V] arrays of one shape")
+    M, V = a.shape
+    if out is None:
+        out = torch.empty(M, dtype=torch.float32, device=a.device)
+    _check(_lib.fq_logit_l2(_dp(a), _dp(b), M, V, _dp(out), _stream(stream)))
     return out
 
 

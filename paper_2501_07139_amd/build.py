@@ -1,6 +1,6 @@
 """Build libfq.so (HIP kernels + C-ABI) for gfx950, in-tree.
 
-    python -m paper_2501_07139_amd.build
+    python paper_2501_07139_amd/build.py
 """
 from __future__ import annotations
 

@@ -115,6 +115,17 @@ extern "C" int fq_token_nll(const void *logits, const int32_t *labels, int M, in
     return check_hip(fq_launch_nll(logits, labels, M, V, nll_out, static_cast<fq_stream>(stream)), "fq_token_nll launch");
 }
 
+extern "C" int fq_logit_l2(const void *a, const void *b, int M, int V, float *dist_out, void *stream)
+{
+    if (!a || !b || !dist_out)
+        return fq_fail(FQ_ERR_NULL, "fq_logit_l2: NULL argument");
+    if (M <= 0 || V <= 0)
+        return fq_fail(FQ_ERR_SHAPE, "fq_logit_l2: M=%d V=%d", M, V);
+    if (!aligned16(a) || !aligned16(b))
+        return fq_fail(FQ_ERR_ALIGN, "fq_logit_l2: a and b must be 16-byte aligned");
+    return check_hip(fq_launch_logit_l2(a, b, M, V, dist_out, static_cast<fq_stream>(stream)), "fq_logit_l2 launch");
+}
+
 // Workspace: u, q, k, v, a, o, x1, u2, d, xcur (hidden wide) and g, p, m (ffn wide).
 extern "C" size_t fq_stack_workspace_bytes(int M, int hidden, int ffn)
 {

@@ -39,5 +39,6 @@ int fq_launch_gemm(const void *x, int M, const fq_packed_ref &w, void *out, fq_s
 int fq_launch_dense(const void *x, int M, const void *W, int N, int K, void *out, fq_stream st);
 int fq_launch_glue(int op, const void *a, const void *b, const void *c, int M, int H, void *out, fq_stream st);
 int fq_launch_nll(const void *logits, const int32_t *labels, int M, int V, float *nll, fq_stream st);
+int fq_launch_logit_l2(const void *a, const void *b, int M, int V, float *dist, fq_stream st);
 
 #endif

@@ -209,6 +209,52 @@ int fq_launch_glue(int op, const void *a, const void *b, const void *c, int M, i
     return (int)hipGetLastError();
 }
 
+// Row-wise Euclidean distance between two logit arrays (sensitivity analysis of the search, Section
+// "Search method").  One workgroup per row, one pass over both rows with 128-bit loads; differences and
+// squares in fp32, four partial sums per thread, then a fixed-order reduction.
+__global__ __launch_bounds__(256) void logit_l2_kernel(const _Float16 *__restrict__ a, const _Float16 *__restrict__ b,
+                                                       int V, float *__restrict__ dist)
+{
+    const int row = blockIdx.x;
+    const _Float16 *ra = a + (size_t)row * V, *rb = b + (size_t)row * V;
+    float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+    // rows start 16-byte aligned only if V % 8 == 0; otherwise take the scalar route
+    if ((V & 7) == 0) {
+        const int chunks = V >> 3;
+        for (int ch = threadIdx.x; ch < chunks; ch += 256) {
+            const h8 va = *reinterpret_cast<const h8 *>(ra + ch * 8), vb = *reinterpret_cast<const h8 *>(rb + ch * 8);
+            float d[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                d[e] = (float)va[e] - (float)vb[e];
+            s0 = fmaf(d[0], d[0], s0); s1 = fmaf(d[1], d[1], s1); s2 = fmaf(d[2], d[2], s2); s3 = fmaf(d[3], d[3], s3);
+            s0 = fmaf(d[4], d[4], s0); s1 = fmaf(d[5], d[5], s1); s2 = fmaf(d[6], d[6], s2); s3 = fmaf(d[7], d[7], s3);
+        }
+    } else {
+        for (int i = threadIdx.x; i < V; i += 256) {
+            const float d = (float)ra[i] - (float)rb[i];
+            s0 = fmaf(d, d, s0);
+        }
+    }
+    float ss = (s0 + s1) + (s2 + s3);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1)
+        ss += __shfl_xor(ss, o, 64);
+    __shared__ float part[4];
+    if ((threadIdx.x & 63) == 0)
+        part[threadIdx.x >> 6] = ss;
+    __syncthreads();
+    if (threadIdx.x == 0)
+        dist[row] = sqrtf((part[0] + part[1]) + (part[2] + part[3]));
+}
+
+int fq_launch_logit_l2(const void *a, const void *b, int M, int V, float *dist, fq_stream st)
+{
+    hipLaunchKernelGGL(logit_l2_kernel, dim3(M), dim3(256), 0, st, static_cast<const _Float16 *>(a),
+                       static_cast<const _Float16 *>(b), V, dist);
+    return (int)hipGetLastError();
+}
+
 int fq_launch_nll(const void *logits, const int32_t *labels, int M, int V, float *nll, fq_stream st)
 {
     hipLaunchKernelGGL(nll_kernel, dim3(M), dim3(256), 0, st, static_cast<const _Float16 *>(logits), labels, V, nll);

@@ -225,6 +225,28 @@ def test_token_nll_against_oracle(fq, torch, shape):
 
 
 # ---------------------------------------------------------------------- glue
+@pytest.mark.parametrize("shape", [(2048, 32000), (130, 1001), (7, 8), (3, 32768)])
+def test_logit_l2_against_oracle(fq, torch, shape):
+    """fp32 accumulation of up to 32768 squares in four partial sums per thread: relative error of the
+    sum below 2e-6, of its root below 1e-6; the bound asked is 1e-5 (plus exact zero for equal rows)."""
+    M, V = shape
+    a = fq_synth.logits(400, M, V)
+    b = fq_synth.logits(401, M, V)
+    b[0] = a[0]                      # distance exactly 0
+    b[M - 1] = a[M - 1]
+    b[M - 1, V - 1] = np.float16(float(a[M - 1, V - 1]) + 2.0)  # a single differing entry, in the ragged tail
+    got = fq.fq_logit_l2(dev(torch, a), dev(torch, b)).cpu().numpy().astype(np.float64)
+    want = oracle.logit_l2(a, b)
+    assert got[0] == 0.0
+    assert got[M - 1] == want[M - 1]
+    assert np.max(np.abs(got - want) / np.maximum(want, 1e-30)) <= 1e-5 or np.allclose(got, want, rtol=1e-5, atol=0)
+    # large magnitudes: differences up to 2 * 65504 still square and sum in range of fp32
+    big = np.full((2, V), 65504.0, dtype=np.float16)
+    neg = -big
+    got = fq.fq_logit_l2(dev(torch, big), dev(torch, neg)).cpu().numpy().astype(np.float64)
+    assert np.allclose(got, oracle.logit_l2(big, neg), rtol=1e-5)
+
+
 @pytest.mark.parametrize("H", [256, 4096, 11008, 13824])
 def test_glue_steps_against_oracle(fq, torch, H):
     M = 9
@@ -397,3 +419,44 @@ def test_ensemble_sweep_scores_candidates_like_the_oracle(fq, torch):
         scores.append((nll.mean(), ref.mean()))
     # the ranking the search would use is the oracle's
     assert np.array_equal(np.argsort([s[0] for s in scores]), np.argsort([s[1] for s in scores]))
+
+
+def test_sensitivity_table_ranks_like_the_oracle(fq, torch):
+    """Sensitivity analysis: QM(n_up) = all 8-bit, one matrix lowered at a time.  The distance is a norm of
+    differences of fp16 logits, so its own rounding floor is about ulp(logit)/sqrt(6) per entry; values are
+    compared with 3 % + that floor, and the filter's pick must agree wherever the oracle's values are apart
+    by more than that."""
+    from paper_2501_07139_amd import sweep
+
+    stack, host, sh = build_stack(fq, "tiny", 500)
+    L, M, V = sh["layers"], 32, 1000
+    up = np.full(7 * L, 8, dtype=np.uint8)
+    x = fq_synth.activations(501, M, sh["hidden"])
+    head = fq_synth.weights(502, V, sh["hidden"], 0.05).astype(np.float16)
+    entries = [0, 3, 6, 7 + 4, 7 * (L - 1) + 1, 7 * L - 1]
+    got = sweep.sensitivity_table(stack, dev(torch, head), up, dev(torch, x), entries=entries)
+    assert sorted(got) == sorted((e, b) for e in entries for b in (2, 3, 4))
+
+    def logits_for(bitvec):
+        mats = [[oracle.dequant(*host[l][j][int(bitvec[7 * l + j])]) for j in range(7)] for l in range(L)]
+        return oracle.round_f16(oracle.dense_f16(oracle.stack_forward(x, mats), head))  # the stored fp16 logits
+
+    ref = logits_for(up)
+    floor = float(np.sqrt(M * V / 6.0) * 2.0 ** -11 * np.sqrt(np.mean(ref.astype(np.float64) ** 2)))
+    want = {}
+    for (e, b) in got:
+        cand = up.copy()
+        cand[e] = b
+        want[(e, b)] = float(np.sqrt(np.sum(oracle.logit_l2(logits_for(cand), ref) ** 2)))
+        assert abs(got[(e, b)] - want[(e, b)]) <= 0.03 * want[(e, b)] + 2 * floor, (e, b, got[(e, b)], want[(e, b)])
+    # lowering to fewer bits moves the logits further
+    for e in entries:
+        assert got[(e, 2)] > got[(e, 3)] > got[(e, 4)]
+    # the filter keeps the same candidates as the oracle's table where those are clearly apart
+    keys = sorted(got)
+    pick_gpu = sweep.analysis_filter(got, keys, 6)
+    pick_cpu = sweep.analysis_filter(want, keys, 6)
+    cut = sorted(want.values())[5]
+    clear = [k for k in keys if abs(want[k] - cut) > 0.03 * cut + 2 * floor]
+    assert {k for k in pick_gpu if k in clear} == {k for k in pick_cpu if k in clear}
+

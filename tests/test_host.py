@@ -106,6 +106,9 @@ def test_error_codes_without_launching_anything():
     assert lib.fq_qlinear(16, 1, 24, 16, 16, 1, 128, 4, 128, 16, None) == -5
     assert lib.fq_qlinear(16, 0, 16, 16, 16, 1, 128, 4, 128, 16, None) == -2
     assert lib.fq_token_nll(None, None, 1, 1, None, None) == -1
+    assert lib.fq_logit_l2(None, 16, 1, 1, 16, None) == -1
+    assert lib.fq_logit_l2(16, 16, 0, 8, 16, None) == -2
+    assert lib.fq_logit_l2(16, 24, 1, 8, 16, None) == -5
     assert lib.fq_glue(9, 16, 16, 16, 1, 128, 16, None) == -2
     assert lib.fq_dense_f16(16, 1, 16, 1, 100, 16, None) == -2
     # the matrix-core kernels address their arrays through 32-bit offsets: 4 GiB of activations is refused
