@@ -1,0 +1,51 @@
+"""Plain reference of the ensemble tree search (FlexQuant, arXiv 2501.07139, Algorithm 1 and the prose of
+Section "Search method").  Test infrastructure: slow, no caching, no GPU; only the tests use it.
+
+Steps, in the paper's order and names, for a beam of #stem paths (the prose's reading of the single list of
+the listing):
+  EQM_last        the last model of every path
+  candidateGenerator   every model obtained from an EQM_last by moving ONE matrix to the next lower stored
+                       bit-width (one-way: never up)
+  analysisFilter  per EQM_last, the #branch candidates whose (matrix, new bits) has the smallest value in the
+                  pre-built sensitivity table
+  calibrationEval the perplexity of a candidate, from the caller's function
+  rank            the pooled candidates (duplicates once, attributed to the first path that produced them)
+                  by perplexity; ties by smaller footprint, then by the bit vector
+  the first #stem become the new EQM_last of their parents' paths
+until no EQM_last has a successor, i.e. all have reached QM(n_low).  Result: the paths, by mean perplexity.
+"""
+import numpy as np
+
+
+def footprint(bits, shapes, group=128):
+    return sum(n * k * int(b) // 8 + 2 * 2 * n * (k // group) for b, (n, k) in zip(bits, shapes))
+
+
+def tree_search_ref(start, levels, sensitivity, calibration_eval, shapes, stems, branches):
+    levels = sorted(levels)
+    start = tuple(int(b) for b in start)
+    paths = [[(start, calibration_eval(start))]]
+    while True:
+        pooled = []  # (candidate, index of the parent path)
+        seen = set()
+        for pi, path in enumerate(paths):
+            last = path[-1][0]
+            cands = []
+            for entry in range(len(last)):
+                pos = levels.index(last[entry])
+                if pos == 0:
+                    continue  # already at n_low
+                lower = levels[pos - 1]
+                cand = list(last)
+                cand[entry] = lower
+                cands.append((sensitivity[(entry, lower)], entry, lower, tuple(cand)))
+            cands.sort()
+            for _, _, _, cand in cands[:branches]:
+                if cand not in seen:
+                    seen.add(cand)
+                    pooled.append((cand, pi))
+        if not pooled:
+            break
+        ranked = sorted((calibration_eval(c), footprint(c, shapes), c, pi) for c, pi in pooled)
+        paths = [paths[pi] + [(c, ppl)] for ppl, _, c, pi in ranked[:stems]]
+    return sorted(paths, key=lambda p: (float(np.mean([ppl for _, ppl in p])), p[-1][0]))

@@ -1,0 +1,130 @@
+"""Tree search for the ensemble of hybrid models (FlexQuant, arXiv 2501.07139, Algorithm 1), as a driver
+over the library's entry points.
+
+An EQM is a bit vector: one stored bit-width per matrix.  From QM(n_up) the search lowers one matrix by one
+stored level per step (transitions are one-way) until QM(n_low) is reached; every step generates the
+successors of the current models, keeps the #branch least sensitive ones per model (analysis filter, from
+the pre-built table of `sweep.sensitivity_table`), scores those on the calibration rows (perplexity) and
+keeps the #stem best as the new current models.
+
+Readings of the text (Algorithm 1 keeps one list where the prose keeps #stem of them): the search is a beam
+of #stem paths; the candidates of all current models form one pool, duplicates are scored once, the pool is
+ranked by perplexity (ties: smaller footprint, then the bit vector itself) and its first #stem members
+become the current models, each remembering its parent.  A current model already at QM(n_low) generates
+nothing; the search ends when the pool is empty.  The output is every surviving path, best first by mean
+perplexity of its members.
+
+All arithmetic of the evaluation runs in the library's kernels (`fq_stack_forward`, `fq_dense_f16`,
+`fq_token_nll`); a candidate differs from its parent in one block, so it is run from that block onwards over
+the parent's cached block inputs.
+"""
+from __future__ import annotations
+
+from typing import Callable, Dict, List, Optional, Sequence, Tuple
+
+import numpy as np
+
+BitVec = Tuple[int, ...]
+
+
+def footprint_bytes(bitvec: Sequence[int], shapes: Sequence[Tuple[int, int]], group: int = 128) -> int:
+    """Packed bytes of a hybrid model: codes plus one fp16 scale and zero per group."""
+    total = 0
+    for b, (n, k) in zip(bitvec, shapes):
+        total += n * k * int(b) // 8 + 4 * n * (k // group)
+    return total
+
+
+def successors(bitvec: BitVec, levels: Sequence[int]) -> List[Tuple[int, int, BitVec]]:
+    """(entry, new bits, new vector) for every entry lowered to the next stored level below its own."""
+    order = sorted(levels)
+    out = []
+    for e, b in enumerate(bitvec):
+        i = order.index(b)
+        if i > 0:
+            nb = order[i - 1]
+            out.append((e, nb, bitvec[:e] + (nb,) + bitvec[e + 1:]))
+    return out
+
+
+class Node:
+    __slots__ = ("bitvec", "ppl", "parent", "state")
+
+    def __init__(self, bitvec: BitVec, ppl: float, parent: Optional["Node"], state=None):
+        self.bitvec, self.ppl, self.parent, self.state = bitvec, ppl, parent, state
+
+    def path(self) -> List["Node"]:
+        n, out = self, []
+        while n is not None:
+            out.append(n)
+            n = n.parent
+        return out[::-1]
+
+
+def tree_search(start: Sequence[int], levels: Sequence[int], sensitivity: Dict[Tuple[int, int], float],
+                evaluate: Callable[[BitVec, Optional[Node], Optional[int]], Tuple[float, object]],
+                shapes: Sequence[Tuple[int, int]], stems: int, branches: int,
+                trace: Optional[list] = None) -> List[List[Node]]:
+    """Algorithm 1.  `evaluate(bitvec, parent, entry)` returns (perplexity, state kept with the node); parent
+    and the changed entry let it reuse the parent's work.  Returns the surviving paths, best first.  If
+    `trace` is a list, every iteration appends its scored pool as [(bitvec, perplexity), ...] in rank order."""
+    start = tuple(int(b) for b in start)
+    ppl0, st0 = evaluate(start, None, None)
+    current = [Node(start, ppl0, None, st0)]
+    while True:
+        pool: Dict[BitVec, Tuple[Node, int]] = {}
+        for node in current:
+            cands = successors(node.bitvec, levels)
+            cands.sort(key=lambda c: (sensitivity[(c[0], c[1])], c[0], c[1]))  # analysis filter
+            for e, nb, vec in cands[:branches]:
+                pool.setdefault(vec, (node, e))  # a duplicate keeps its first parent
+        if not pool:
+            break
+        scored = []
+        for vec, (parent, e) in pool.items():
+            ppl, st = evaluate(vec, parent, e)
+            scored.append(Node(vec, ppl, parent, st))
+        scored.sort(key=lambda n: (n.ppl, footprint_bytes(n.bitvec, shapes), n.bitvec))
+        if trace is not None:
+            trace.append([(n.bitvec, n.ppl) for n in scored])
+        for n in scored[stems:]:
+            n.state = None
+        for n in current:
+            n.state = None  # the parents' cached inputs are no longer needed
+        current = scored[:stems]
+    paths = [n.path() for n in current]
+    paths.sort(key=lambda p: (float(np.mean([n.ppl for n in p])), p[-1].bitvec))
+    return paths
+
+
+class CalibrationEval:
+    """calibrationEval of Algorithm 1 on the GPU: perplexity of a hybrid model over the calibration rows,
+    exp(mean token NLL).  Keeps the input of every block with the node so that a successor restarts at the
+    block it changes."""
+
+    def __init__(self, stack, head, x, labels):
+        import torch
+
+        from . import Stack, fq_stack_workspace_bytes
+
+        self.stack, self.head, self.x, self.labels = stack, head, x, labels
+        self.L = stack.L
+        self.one = [Stack([stack.layers[l]]) for l in range(self.L)]
+        M = x.shape[0]
+        self.ws = torch.empty(fq_stack_workspace_bytes(M, stack.hidden, stack.ffn), dtype=torch.uint8, device=x.device)
+        self.evaluations = 0
+        self.blocks_run = 0
+
+    def __call__(self, bitvec: BitVec, parent: Optional[Node], entry: Optional[int]):
+        from . import fq_dense_f16, fq_stack_forward, fq_token_nll
+
+        bv = np.asarray(bitvec, dtype=np.uint8)
+        first = 0 if parent is None or parent.state is None else entry // 7
+        inputs = [self.x] if first == 0 else list(parent.state[:first + 1])
+        for l in range(first, self.L):
+            inputs.append(fq_stack_forward(self.one[l], bv[7 * l:7 * l + 7], inputs[l], workspace=self.ws))
+        logits = fq_dense_f16(inputs[self.L], self.head)
+        nll = fq_token_nll(logits, self.labels).cpu().numpy().astype(np.float64)
+        self.evaluations += 1
+        self.blocks_run += self.L - first
+        return float(np.exp(nll.mean())), inputs

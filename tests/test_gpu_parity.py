@@ -460,3 +460,57 @@ def test_sensitivity_table_ranks_like_the_oracle(fq, torch):
     clear = [k for k in keys if abs(want[k] - cut) > 0.03 * cut + 2 * floor]
     assert {k for k in pick_gpu if k in clear} == {k for k in pick_cpu if k in clear}
 
+
+def test_tree_search_on_the_gpu_makes_choices_the_oracle_agrees_with(fq, torch):
+    """Algorithm 1 driven by the GPU evaluator on a small stack.  Every scored candidate's perplexity must
+    match the oracle's within 2e-3 relative (per-sequence NLL bound 1e-3, a little slack for exp), and every
+    iteration must keep a set of models that is a correct top-#stem under the oracle's values up to such
+    near-ties; the path itself must obey the one-way, one-matrix-per-step rule and end at QM(n_low)."""
+    from paper_2501_07139_amd import search, sweep
+
+    levels = (2, 4, 8)
+    stack, host, sh = build_stack(fq, "tiny", 600, bit_choices=levels)
+    L, M, V = sh["layers"], 64, 1000
+    shapes = fq_synth.block_matrix_shapes(sh["hidden"], sh["ffn"]) * L
+    x = fq_synth.activations(601, M, sh["hidden"])
+    head = fq_synth.weights(602, V, sh["hidden"], 0.05).astype(np.float16)
+    labels = fq_synth.labels(603, M, V)
+    up = np.full(7 * L, 8, dtype=np.uint8)
+    xd, hd, ld = dev(torch, x), dev(torch, head), torch.from_numpy(labels).cuda()
+    table = sweep.sensitivity_table(stack, hd, up, xd)
+    assert len(table) == 7 * L * 2
+    ev = search.CalibrationEval(stack, hd, xd, ld)
+    trace = []
+    stems, branches = 2, 3
+    paths = search.tree_search(up, levels, table, ev, shapes, stems, branches, trace=trace)
+    assert len(trace) == 7 * L * 2                      # (levels - 1) steps per matrix
+    assert ev.blocks_run < ev.evaluations * L           # successors restart at the block they change
+    for path in paths:
+        assert path[-1].bitvec == (2,) * (7 * L)
+        for a, b in zip(path, path[1:]):
+            assert sum(p != q for p, q in zip(a.bitvec, b.bitvec)) == 1 and all(q <= p for p, q in zip(a.bitvec, b.bitvec))
+
+    deq = {}
+
+    def oracle_ppl(bits):
+        mats = []
+        for l in range(L):
+            row = []
+            for j in range(7):
+                key = (l, j, bits[7 * l + j])
+                if key not in deq:
+                    deq[key] = oracle.dequant(*host[l][j][bits[7 * l + j]])
+                row.append(deq[key])
+            mats.append(row)
+        logits = oracle.round_f16(oracle.dense_f16(oracle.stack_forward(x, mats), head))
+        return oracle.perplexity(oracle.token_nll(logits, labels))
+
+    for it in trace[::6] + trace[-2:]:                  # a sample of the iterations, incl. the last ones
+        want = {b: oracle_ppl(b) for b, _ in it}
+        for b, p in it:
+            assert abs(p - want[b]) <= 2e-3 * want[b], (b, p, want[b])
+        kept = [b for b, _ in it[:stems]]
+        cut = sorted(want.values())[min(stems, len(it)) - 1]
+        for b in kept:                                  # nothing kept is clearly worse than the oracle's cut
+            assert want[b] <= cut * (1 + 4e-3)
+
