@@ -49,3 +49,30 @@ def tree_search_ref(start, levels, sensitivity, calibration_eval, shapes, stems,
         ranked = sorted((calibration_eval(c), footprint(c, shapes), c, pi) for c, pi in pooled)
         paths = [paths[pi] + [(c, ppl)] for ppl, _, c, pi in ranked[:stems]]
     return sorted(paths, key=lambda p: (float(np.mean([ppl for _, ppl in p])), p[-1][0]))
+
+
+def prune_ref(ensemble, levels, shapes, rate):
+    """Section "EQM Pruning Strategy", written out plainly: count, per stored mid-level packing
+    (matrix, bits), the models of the ensemble that use it; rank by count (more first), equal counts by the
+    mean footprint of the using models (lower first), never-used packings last; drop the bottom `rate`
+    share; what stays stored is every n_low and n_up packing plus the kept mid-level ones."""
+    levels = sorted(levels)
+    mids = levels[1:-1]
+    rows = []
+    for entry in range(len(shapes)):
+        for bits in mids:
+            users = [footprint(m, shapes) for m in ensemble if m[entry] == bits]
+            mean_fp = sum(users) / len(users) if users else float("inf")
+            rows.append((-len(users), mean_fp, entry, bits))
+    rows.sort()
+    ranking = [(entry, bits) for _, _, entry, bits in rows]
+    ndrop = int(rate * len(ranking) + 1e-9)
+    dropped = set(ranking[len(ranking) - ndrop:]) if ndrop else set()
+    kept = [m for m in ensemble if all((e, b) not in dropped for e, b in enumerate(m))]
+    stored = 0
+    for entry, shape in enumerate(shapes):
+        for bits in levels:
+            if (entry, bits) not in dropped:
+                stored += footprint((bits,), [shape])
+    return ranking, dropped, kept, stored
+

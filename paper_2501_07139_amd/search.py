@@ -97,6 +97,39 @@ def tree_search(start: Sequence[int], levels: Sequence[int], sensitivity: Dict[T
     return paths
 
 
+def prune_ensemble(ensemble: Sequence[BitVec], levels: Sequence[int], shapes: Sequence[Tuple[int, int]],
+                   rate: float):
+    """Pruning of the stored mid-level packings (Section "EQM Pruning Strategy").
+
+    Every packing (matrix, bits) with bits strictly between n_low and n_up is ranked by the number of models
+    of the ensemble that use it; equal counts are ordered by the footprint at which they are used (mean over
+    the using models, lower footprints first, since perplexity is most sensitive there); unused packings
+    come last.  The lowest `rate` share of that ranking is dropped.  Returns (ranking best first, dropped
+    set, models of the ensemble that need no dropped packing, stored bytes after pruning)."""
+    order = sorted(levels)
+    mids = order[1:-1]
+    entries = len(shapes)
+    use: Dict[Tuple[int, int], List[int]] = {(e, b): [] for e in range(entries) for b in mids}
+    for vec in ensemble:
+        f = footprint_bytes(vec, shapes)
+        for e, b in enumerate(vec):
+            if b in mids:
+                use[(e, int(b))].append(f)
+    def key(item):
+        (e, b), fs = item
+        return (-len(fs), float(np.mean(fs)) if fs else float("inf"), e, b)
+    ranking = [k for k, _ in sorted(use.items(), key=key)]
+    ndrop = int(np.floor(rate * len(ranking) + 1e-9))
+    dropped = set(ranking[len(ranking) - ndrop:]) if ndrop else set()
+    kept_models = [vec for vec in ensemble if not any((e, int(b)) in dropped for e, b in enumerate(vec))]
+    stored = 0
+    for e, (n, k) in enumerate(shapes):
+        for b in order:
+            if (e, b) not in dropped:
+                stored += footprint_bytes((b,), [(n, k)])
+    return ranking, dropped, kept_models, stored
+
+
 class CalibrationEval:
     """calibrationEval of Algorithm 1 on the GPU: perplexity of a hybrid model over the calibration rows,
     exp(mean token NLL).  Keeps the input of every block with the node so that a successor restarts at the

@@ -118,3 +118,40 @@ def test_footprint_accounting():
     # one MLP matrix from 8 to 2 bits: 45.1 M weights * 6 bits = 33.8 MB, inside the ~100 MB granularity target
     d = search.footprint_bytes((8,) * 7, shapes) - search.footprint_bytes((8, 8, 8, 8, 2, 8, 8), shapes)
     assert d == 11008 * 4096 * 6 // 8
+
+
+@pytest.mark.parametrize("rate", [0.0, 0.25, 0.5, 0.75, 1.0])
+def test_pruning_follows_the_reference_and_the_papers_storage_arithmetic(rate):
+    entries = 8
+    shapes, sens, ppl = synthetic_problem(21, entries)
+    path = search.tree_search((8,) * entries, LEVELS, sens, lambda b, p, e: (ppl(b), None), shapes, 1, 3)[0]
+    ensemble = [n.bitvec for n in path]
+    got = search.prune_ensemble(ensemble, LEVELS, shapes, rate)
+    want = search_ref.prune_ref(ensemble, LEVELS, shapes, rate)
+    assert got[0] == want[0] and got[1] == want[1] and got[2] == want[2] and got[3] == want[3]
+    ranking, dropped, kept, stored = got
+    assert len(ranking) == entries * 2 and len(dropped) == int(rate * entries * 2)
+    # the end points never depend on a mid-level packing
+    assert ensemble[0] in kept and ensemble[-1] in kept
+    # storage: all four packings at rate 0, only n_low and n_up at rate 1, linear in the dropped bytes
+    full = sum(search.footprint_bytes((b,) * entries, shapes) for b in LEVELS)
+    ends = sum(search.footprint_bytes((b,) * entries, shapes) for b in (2, 8))
+    assert stored == full - sum(search.footprint_bytes((b,), [shapes[e]]) for e, b in dropped)
+    if rate == 0.0:
+        assert stored == full and kept == ensemble
+    if rate == 1.0:
+        assert stored == ends and all(set(m) <= {2, 8} for m in kept)
+    # what is dropped is used by no more models than anything that is kept
+    count = lambda k: sum(m[k[0]] == k[1] for m in ensemble)
+    if dropped and len(dropped) < len(ranking):
+        assert max(count(k) for k in dropped) <= min(count(k) for k in ranking if k not in dropped)
+
+
+def test_pruning_tie_break_prefers_use_at_low_footprints():
+    shapes = [(64, 128)] * 3
+    # matrices 0 and 1 are each used once at 4 bits; matrix 1's use happens in the smaller model
+    ensemble = [(8, 8, 8), (4, 8, 8), (2, 8, 8), (2, 4, 8), (2, 2, 8), (2, 2, 2)]
+    ranking, dropped, kept, _ = search.prune_ensemble(ensemble, (2, 4, 8), shapes, 1 / 3)
+    assert ranking == [(1, 4), (0, 4), (2, 4)]       # equal counts: lower footprint first; unused last
+    assert dropped == {(2, 4)} and kept == ensemble
+
