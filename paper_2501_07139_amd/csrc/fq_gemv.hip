@@ -791,15 +791,12 @@ int fq_launch_gemv_multi(const fq_gemv_input &src, int M, const fq_packed_ref *w
     GemvJobs jobs;
     jobs.count = count;
     size_t lds = 0;
-    double bytes[3], total = 0;
     int nrb[3], sum_nrb = 0;
     for (int i = 0; i < count; ++i) {
         const size_t need = gemv_stream_lds(M, w[i].K, w[i].bits, inputs);
         lds = lds > need ? lds : need;
         nrb[i] = ((w[i].N + 63) / 64 * 64) / rows_per_supertile(w[i].bits);
         sum_nrb += nrb[i];
-        bytes[i] = (double)w[i].N * w[i].K * w[i].bits;
-        total += bytes[i];
     }
     int slot = 0, resident = 0;
     const GemvKernel kernel = gemv_kernel_for(src.mode, M, &slot);
@@ -827,22 +824,35 @@ int fq_launch_gemv_multi(const fq_gemv_input &src, int M, const fq_packed_ref *w
     int grid = sum_nrb < resident ? sum_nrb : resident;
     if (grid < count)
         grid = count;
-    // share the workgroups among the matrices in proportion to their packed bytes
-    int left = grid, blk0 = 0;
+    // Share the workgroups among the matrices so that the slowest finishes as early as possible: a
+    // workgroup's time is its number of supertile rows times the cost of a row, which grows with the
+    // bit-width more slowly than the bytes do (2-bit rows are bound by the unpack, not by their bytes).
+    // Start with one workgroup each and hand the others, one at a time, to the matrix that is slowest.
+    static const double row_cost[9] = {0, 0, 1.25, 2.5, 1.0, 0, 0, 0, 1.55}; // per supertile row, relative, by bits
+    int nbs[3] = {1, 1, 1};
+    for (int left = grid - count; left > 0; --left) {
+        int worst = -1;
+        double worst_t = -1.0;
+        for (int i = 0; i < count; ++i) {
+            if (nbs[i] >= nrb[i])
+                continue;
+            const double t = (double)((nrb[i] + nbs[i] - 1) / nbs[i]) * row_cost[w[i].bits];
+            if (t > worst_t) {
+                worst_t = t;
+                worst = i;
+            }
+        }
+        if (worst < 0)
+            break;
+        ++nbs[worst];
+    }
+    int blk0 = 0;
     for (int i = 0; i < count; ++i) {
-        int nb = (i == count - 1) ? left : (int)(grid * bytes[i] / total + 0.5);
-        const int reserve = count - 1 - i; // one workgroup at least for every later matrix
-        if (nb > left - reserve)
-            nb = left - reserve;
-        if (nb > nrb[i])
-            nb = nrb[i];
-        if (nb < 1)
-            nb = 1;
+        const int nb = nbs[i];
         jobs.j[i] = GemvJob{static_cast<const uint32_t *>(w[i].packed), static_cast<const _Float16 *>(w[i].scales),
                             static_cast<const _Float16 *>(w[i].zeros), static_cast<_Float16 *>(outs[i]), w[i].N,
                             w[i].bits, blk0, nb, 0};
         blk0 += nb;
-        left -= nb;
     }
     for (int i = count; i < 3; ++i)
         jobs.j[i] = GemvJob{nullptr, nullptr, nullptr, nullptr, 0, 0, blk0, 0, 0};
