@@ -802,41 +802,42 @@ int fq_launch_gemv_multi(const fq_gemv_input &src, int M, const fq_packed_ref *w
     const GemvKernel kernel = gemv_kernel_for(src.mode, M, &slot);
     if (int e = gemv_resident_blocks(kernel, slot, lds, &resident))
         return e;
-    // A lone 2- or 3-bit matrix with so few supertile rows that half the chip would idle is handed out
-    // by 16-row sub-blocks instead (2 or 4 per supertile row).  The workgroups that then share a
-    // supertile row run at the same time on one XCD, so its L2 fetches their common lines once.
-    if (count == 1 && (w[0].bits == 2 || w[0].bits == 3) && 2 * nrb[0] <= resident) {
-        const int parts = w[0].bits == 2 ? 2 : 4;
-        const int units = (nrb[0] + 7) / 8 * 8 * parts;
-        int nb = (units < resident ? units : resident) / 8 * 8;
-        if (nb < 8)
-            nb = 8;
-        jobs.j[0] = GemvJob{static_cast<const uint32_t *>(w[0].packed), static_cast<const _Float16 *>(w[0].scales),
-                            static_cast<const _Float16 *>(w[0].zeros), static_cast<_Float16 *>(outs[0]), w[0].N,
-                            w[0].bits, 0, nb, 1};
-        for (int i = 1; i < 3; ++i)
-            jobs.j[i] = GemvJob{nullptr, nullptr, nullptr, nullptr, 0, 0, nb, 0, 0};
-        const GemvInput in = {static_cast<const _Float16 *>(src.a), static_cast<const _Float16 *>(src.b),
-                              static_cast<const _Float16 *>(src.c), static_cast<_Float16 *>(src.aux), src.mode};
-        hipLaunchKernelGGL(kernel, dim3(nb), dim3(64 * GNW), lds, st, in, M, w[0].K, jobs);
-        return (int)hipGetLastError();
+    // Work units.  Whole supertile rows as a rule; but when even the 16-row sub-blocks of the 2- and 3-bit
+    // matrices (2 or 4 per supertile row) are no more than the resident workgroups, those matrices are
+    // handed out by sub-block, one per workgroup: 4096 x 4096 at 2 bits has only 128 supertile rows, at
+    // 3 bits 64, and half or more of the chip would idle.  (With more sub-blocks than workgroups the split
+    // loses: a sub-block item carries the fixed cost of a whole one.)  The workgroups that share a
+    // supertile row are 8 apart in the grid, i.e. run on one XCD, whose L2 fetches their common lines
+    // once; the job's share of the grid is a multiple of 8 * parts.
+    int split_units = 0;
+    for (int i = 0; i < count; ++i) {
+        const int f = w[i].bits == 2 ? 2 : (w[i].bits == 3 ? 4 : 1);
+        split_units += f > 1 ? (nrb[i] + 7) / 8 * 8 * f : nrb[i];
     }
-    int grid = sum_nrb < resident ? sum_nrb : resident;
-    if (grid < count)
-        grid = count;
-    // Share the workgroups among the matrices so that the slowest finishes as early as possible: a
-    // workgroup's time is its number of supertile rows times the cost of a row, which grows with the
-    // bit-width more slowly than the bytes do (2-bit rows are bound by the unpack, not by their bytes).
-    // Start with one workgroup each and hand the others, one at a time, to the matrix that is slowest.
-    static const double row_cost[9] = {0, 0, 1.25, 2.5, 1.0, 0, 0, 0, 1.55}; // per supertile row, relative, by bits
-    int nbs[3] = {1, 1, 1};
-    for (int left = grid - count; left > 0; --left) {
+    const bool underfull = split_units <= resident;
+    int parts[3], units[3], gran[3], nbs[3], order[3];
+    double unit_cost[3];
+    // cost of a whole supertile row relative to a 4-bit one (2-bit rows are bound by the unpack, not by
+    // their bytes, so cost grows more slowly than bytes)
+    static const double row_cost[9] = {0, 0, 1.25, 2.5, 1.0, 0, 0, 0, 1.55};
+    int used = 0;
+    for (int i = 0; i < count; ++i) {
+        const int f = w[i].bits == 2 ? 2 : (w[i].bits == 3 ? 4 : 1);
+        parts[i] = (underfull && f > 1) ? f : 1;
+        units[i] = parts[i] > 1 ? (nrb[i] + 7) / 8 * 8 * parts[i] : nrb[i];
+        gran[i] = parts[i] > 1 ? 8 * parts[i] : 1;
+        unit_cost[i] = row_cost[w[i].bits] / parts[i];
+        nbs[i] = gran[i];
+        used += gran[i];
+    }
+    // Hand the remaining workgroups, a granule at a time, to the matrix that would finish last.
+    for (;;) {
         int worst = -1;
         double worst_t = -1.0;
         for (int i = 0; i < count; ++i) {
-            if (nbs[i] >= nrb[i])
+            if (nbs[i] >= units[i] || used + gran[i] > resident)
                 continue;
-            const double t = (double)((nrb[i] + nbs[i] - 1) / nbs[i]) * row_cost[w[i].bits];
+            const double t = (double)((units[i] + nbs[i] - 1) / nbs[i]) * unit_cost[i];
             if (t > worst_t) {
                 worst_t = t;
                 worst = i;
@@ -844,15 +845,22 @@ int fq_launch_gemv_multi(const fq_gemv_input &src, int M, const fq_packed_ref *w
         }
         if (worst < 0)
             break;
-        ++nbs[worst];
+        nbs[worst] += gran[worst];
+        used += gran[worst];
     }
+    // split jobs first: their first workgroup must sit at a multiple of 8
+    int n_order = 0;
+    for (int pass = 0; pass < 2; ++pass)
+        for (int i = 0; i < count; ++i)
+            if ((parts[i] > 1) == (pass == 0))
+                order[n_order++] = i;
     int blk0 = 0;
-    for (int i = 0; i < count; ++i) {
-        const int nb = nbs[i];
-        jobs.j[i] = GemvJob{static_cast<const uint32_t *>(w[i].packed), static_cast<const _Float16 *>(w[i].scales),
+    for (int k = 0; k < count; ++k) {
+        const int i = order[k];
+        jobs.j[k] = GemvJob{static_cast<const uint32_t *>(w[i].packed), static_cast<const _Float16 *>(w[i].scales),
                             static_cast<const _Float16 *>(w[i].zeros), static_cast<_Float16 *>(outs[i]), w[i].N,
-                            w[i].bits, blk0, nb, 0};
-        blk0 += nb;
+                            w[i].bits, blk0, nbs[i], parts[i] > 1 ? 1 : 0};
+        blk0 += nbs[i];
     }
     for (int i = count; i < 3; ++i)
         jobs.j[i] = GemvJob{nullptr, nullptr, nullptr, nullptr, 0, 0, blk0, 0, 0};
