@@ -791,12 +791,11 @@ int fq_launch_gemv_multi(const fq_gemv_input &src, int M, const fq_packed_ref *w
     GemvJobs jobs;
     jobs.count = count;
     size_t lds = 0;
-    int nrb[3], sum_nrb = 0;
+    int nrb[3];
     for (int i = 0; i < count; ++i) {
         const size_t need = gemv_stream_lds(M, w[i].K, w[i].bits, inputs);
         lds = lds > need ? lds : need;
         nrb[i] = ((w[i].N + 63) / 64 * 64) / rows_per_supertile(w[i].bits);
-        sum_nrb += nrb[i];
     }
     int slot = 0, resident = 0;
     const GemvKernel kernel = gemv_kernel_for(src.mode, M, &slot);
