@@ -174,7 +174,9 @@ int fq_glue(int op, const void *a, const void *b, const void *c, int M, int H, v
  * Unquantized fp16 linear (the vocabulary head): out[m,n] = sum_k x[m,k] W[n,k],
  * fp32 accumulation, fp16 output.  x [M,K], W [N,K], out [M,N] row-major,
  * device.  K must be a multiple of 128; x and W must each stay below 4 GiB
- * (FQ_ERR_SHAPE otherwise).
+ * (FQ_ERR_SHAPE otherwise).  Two kernels serve it: 128-row tiles, and 256-row
+ * tiles with both operands in LDS once those fill the chip; the environment
+ * variable FQ_DENSE_TILE=128|256, read at every call, pins one (tests, tuning).
  */
 int fq_dense_f16(const void *x, int M, const void *W, int N, int K, void *out, void *stream);
 

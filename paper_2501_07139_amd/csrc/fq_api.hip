@@ -88,6 +88,12 @@ extern "C" int fq_dense_f16(const void *x, int M, const void *W, int N, int K, v
         return fq_fail(FQ_ERR_ALIGN, "fq_dense_f16: pointers must be 16-byte aligned");
     if (!below_4gib(M, K, 2) || !below_4gib(N, K, 2))
         return fq_fail(FQ_ERR_SHAPE, "fq_dense_f16: M=%d N=%d K=%d: x and W must each stay below 4 GiB", M, N, K);
+    // FQ_DENSE_TILE=128 or 256 in the environment pins the kernel (tests of either at any size)
+    const char *pin = getenv("FQ_DENSE_TILE");
+    const bool tiled = pin && *pin ? atoi(pin) == 256 : fq_dense_tiled_pays(M, N);
+    if (tiled)
+        return check_hip(fq_launch_dense_tiled(x, M, W, N, K, out, static_cast<fq_stream>(stream)),
+                         "fq_dense_f16 launch");
     return check_hip(fq_launch_dense(x, M, W, N, K, out, static_cast<fq_stream>(stream)), "fq_dense_f16 launch");
 }
 

@@ -37,6 +37,9 @@ int fq_launch_gemv_multi(const fq_gemv_input &src, int M, const fq_packed_ref *w
                          fq_stream st);
 int fq_launch_gemm(const void *x, int M, const fq_packed_ref &w, void *out, fq_stream st);
 int fq_launch_dense(const void *x, int M, const void *W, int N, int K, void *out, fq_stream st);
+// The same product with 256 x 256 tiles, both operands through LDS; pays once its tiles fill the chip.
+bool fq_dense_tiled_pays(int M, int N);
+int fq_launch_dense_tiled(const void *x, int M, const void *W, int N, int K, void *out, fq_stream st);
 int fq_launch_glue(int op, const void *a, const void *b, const void *c, int M, int H, void *out, fq_stream st);
 int fq_launch_nll(const void *logits, const int32_t *labels, int M, int V, float *nll, fq_stream st);
 int fq_launch_logit_l2(const void *a, const void *b, int M, int V, float *dist, fq_stream st);

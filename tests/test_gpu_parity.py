@@ -181,15 +181,21 @@ def test_more_bits_track_the_unquantized_layer_better_on_gpu(fq, torch):
 
 
 # --------------------------------------------------------------- dense head
-@pytest.mark.parametrize("case", [(40, 512, 256), (300, 1000, 384), (2048, 32000, 512)], ids=str)
-def test_dense_head_against_oracle(fq, torch, case):
+@pytest.mark.parametrize("tile", ["auto", "128", "256"])
+@pytest.mark.parametrize("case", [(40, 512, 256), (300, 1000, 384), (257, 1026, 128), (2048, 32000, 512)], ids=str)
+def test_dense_head_against_oracle(fq, torch, case, tile, monkeypatch):
+    """Both kernels behind fq_dense_f16 (128- and 256-row tiles), pinned through the environment, and the
+    library's own choice; ragged sizes cover rows and columns past the last full tile."""
     M, N, K = case
+    if tile != "auto":
+        monkeypatch.setenv("FQ_DENSE_TILE", tile)
     X = fq_synth.activations(13, M, K)
     W = fq_synth.weights(14, N, K).astype(np.float16)
     y = host16(fq.fq_dense_f16(dev(torch, X), dev(torch, W)))
     if M * N > 1 << 20:
         rng = np.random.default_rng(0)
-        rows, cols = np.unique(rng.integers(0, M, 40)), np.unique(rng.integers(0, N, 300))
+        rows = np.unique(np.concatenate([rng.integers(0, M, 40), [0, M - 1]]))
+        cols = np.unique(np.concatenate([rng.integers(0, N, 300), [0, N - 1]]))
         r = oracle.dense_f16(X[rows], W[cols])
         assert qerr(y[np.ix_(rows, cols)], r) <= TOL
     else:
