@@ -191,6 +191,24 @@ int fq_dense_f16(const void *x, int M, const void *W, int N, int K, void *out, v
 int fq_token_nll(const void *logits, const int32_t *labels, int M, int V, float *nll_out, void *stream);
 
 /*
+ * The two steps above in one: token losses of the head's logits without storing
+ * the logits (calibrationEval of Algorithm 1 needs only the losses),
+ *   nll[m] = fq_token_nll(round_fp16(fq_dense_f16(x, W)), labels)[m],
+ * the logits rounded to fp16 exactly as fq_dense_f16 would store them.  Every
+ * workgroup of the GEMM reduces its tile of logits to one (maximum, sum of
+ * exponentials) pair per row and 64 columns; a second kernel merges the pairs.
+ * x fp16 [M,K], W fp16 [V,K], labels int32 [M]: device, read.  nll fp32 [M]:
+ * device, written.  workspace: device scratch of at least
+ * fq_head_nll_workspace_bytes(M, V) bytes, 16-byte aligned, owned by the caller,
+ * contents undefined afterwards (FQ_ERR_WORKSPACE if NULL or too small).
+ * K a multiple of 128; x and W below 4 GiB each (FQ_ERR_SHAPE).  Always runs the
+ * 256-row tiles: meant for M * V large enough to fill the chip.
+ */
+size_t fq_head_nll_workspace_bytes(int M, int V);
+int fq_head_nll(const void *x, int M, const void *W, int V, int K, const int32_t *labels, float *nll_out,
+                void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Row-wise Euclidean distance between two sets of logits (Section "Search
  * method": the sensitivity value of a module is the Euclidean distance between
  * the logits of the hybrid model with that module lowered and those of

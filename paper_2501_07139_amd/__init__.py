@@ -64,6 +64,8 @@ def _load() -> ctypes.CDLL:
         "fq_dense_f16": (ci, [vp, ci, vp, ci, ci, vp, vp]),
         "fq_token_nll": (ci, [vp, vp, ci, ci, vp, vp]),
         "fq_logit_l2": (ci, [vp, vp, ci, ci, vp, vp]),
+        "fq_head_nll_workspace_bytes": (sz, [ci, ci]),
+        "fq_head_nll": (ci, [vp, ci, vp, ci, ci, vp, vp, vp, sz, vp]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -75,7 +77,7 @@ def _load() -> ctypes.CDLL:
 _lib = _load()
 EXPORTS = ("fq_last_error", "fq_version", "fq_quantize_rtn", "fq_packed_bytes", "fq_meta_count", "fq_pack_groups",
            "fq_dequant", "fq_qlinear", "fq_stack_workspace_bytes", "fq_stack_forward", "fq_glue", "fq_dense_f16",
-           "fq_token_nll", "fq_logit_l2")
+           "fq_token_nll", "fq_logit_l2", "fq_head_nll_workspace_bytes", "fq_head_nll")
 
 
 def _check(rc: int) -> None:
@@ -286,6 +288,28 @@ def fq_logit_l2(a, b, out=None, stream=None):
     if out is None:
         out = torch.empty(M, dtype=torch.float32, device=a.device)
     _check(_lib.fq_logit_l2(_dp(a), _dp(b), M, V, _dp(out), _stream(stream)))
+    return out
+
+
+def fq_head_nll_workspace_bytes(M: int, V: int) -> int:
+    return _lib.fq_head_nll_workspace_bytes(M, V)
+
+
+def fq_head_nll(x, W, labels, out=None, workspace=None, stream=None):
+    torch = _torch()
+    x = _dev(x, torch.float16, "x")
+    W = _dev(W, torch.float16, "W")
+    labels = _dev(labels, torch.int32, "labels")
+    M, K = x.shape
+    V = W.shape[0]
+    if W.shape[1] != K or labels.numel() != M:
+        raise ValueError("fq_head_nll: x [M,K], W [V,K], labels [M]")
+    if out is None:
+        out = torch.empty(M, dtype=torch.float32, device=x.device)
+    if workspace is None:
+        workspace = torch.empty(fq_head_nll_workspace_bytes(M, V), dtype=torch.uint8, device=x.device)
+    _check(_lib.fq_head_nll(_dp(x), M, _dp(W), V, K, _dp(labels), _dp(out), _dp(workspace), workspace.numel(),
+                            _stream(stream)))
     return out
 
 

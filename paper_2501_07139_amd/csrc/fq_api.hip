@@ -121,6 +121,31 @@ extern "C" int fq_token_nll(const void *logits, const int32_t *labels, int M, in
     return check_hip(fq_launch_nll(logits, labels, M, V, nll_out, static_cast<fq_stream>(stream)), "fq_token_nll launch");
 }
 
+extern "C" size_t fq_head_nll_workspace_bytes(int M, int V)
+{
+    if (M <= 0 || V <= 0)
+        return 0;
+    return (fq_head_nll_scratch_bytes(M, V) + 15) / 16 * 16;
+}
+
+extern "C" int fq_head_nll(const void *x, int M, const void *W, int V, int K, const int32_t *labels, float *nll_out,
+                           void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!x || !W || !labels || !nll_out)
+        return fq_fail(FQ_ERR_NULL, "fq_head_nll: NULL argument");
+    if (M <= 0 || V <= 0 || K <= 0 || K % 128 != 0)
+        return fq_fail(FQ_ERR_SHAPE, "fq_head_nll: M=%d V=%d K=%d (K must be a positive multiple of 128)", M, V, K);
+    if (!below_4gib(M, K, 2) || !below_4gib(V, K, 2))
+        return fq_fail(FQ_ERR_SHAPE, "fq_head_nll: M=%d V=%d K=%d: x and W must each stay below 4 GiB", M, V, K);
+    if (!workspace || workspace_bytes < fq_head_nll_workspace_bytes(M, V))
+        return fq_fail(FQ_ERR_WORKSPACE, "fq_head_nll: workspace of %zu bytes, need %zu", workspace ? workspace_bytes : 0,
+                       fq_head_nll_workspace_bytes(M, V));
+    if (!aligned16(x) || !aligned16(W) || !aligned16(workspace))
+        return fq_fail(FQ_ERR_ALIGN, "fq_head_nll: x, W and workspace must be 16-byte aligned");
+    return check_hip(fq_launch_head_nll(x, M, W, V, K, labels, nll_out, workspace, static_cast<fq_stream>(stream)),
+                     "fq_head_nll launch");
+}
+
 extern "C" int fq_logit_l2(const void *a, const void *b, int M, int V, float *dist_out, void *stream)
 {
     if (!a || !b || !dist_out)

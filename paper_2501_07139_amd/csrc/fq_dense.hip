@@ -10,8 +10,14 @@
 // row-major with the eight 16-byte chunks of a row XOR-swizzled by (row / 2) % 8: the copy writes whole
 // rows and the operand reads of sixteen rows by one chunk touch every bank once.  The copy of iteration
 // kt+1 is issued before the MFMAs of iteration kt; one barrier per iteration.
+//
+// Fused loss (the same calibrationEval, logits never stored): instead of writing its 128 x 64 logits a
+// wavefront rounds them to fp16, as the stored logits would be, and reduces every row to the pair
+// (maximum, sum of exp(logit - maximum)) over its 64 columns; a second small kernel merges a row's pairs
+// over the vocabulary and subtracts the label's logit, which the one lane that holds it has set aside.
 #include "fq_device.h"
 #include "fq_internal.h"
+#include "fq_lse.h"
 
 namespace {
 
@@ -21,9 +27,17 @@ constexpr int DSLOTS = DT * 8; // 16-byte slots of one operand tile
 
 __device__ __forceinline__ int dense_slot(int row, int ch) { return row * 8 + (ch ^ ((row >> 1) & 7)); }
 
+// What the fused-loss variant writes instead of logits.
+struct LossParts {
+    const int32_t *labels; // [M]
+    float2 *pairs;         // [M][ceil(N / 64)]: (maximum, sum of exp(logit - maximum)) of 64 columns
+    float *label_logit;    // [M]: the label's logit, written only where the label is in range
+};
+
+template <bool FUSED>
 __global__ __launch_bounds__(512, 2) void dense_kernel(const _Float16 *__restrict__ x, int M,
                                                        const _Float16 *__restrict__ W, int N, int K,
-                                                       _Float16 *__restrict__ out)
+                                                       _Float16 *__restrict__ out, LossParts loss)
 {
     __shared__ h8 tiles[2][2][DSLOTS]; // [buffer][0: activations, 1: weights]
 
@@ -100,7 +114,43 @@ __global__ __launch_bounds__(512, 2) void dense_kernel(const _Float16 *__restric
         __syncthreads();                            // ... and everyone's, and all reads of `cur` are done
     }
 
-    // store: lane holds m = lane%16 and n = 4*(lane/16) + v of each 16x16 block
+    // lane holds m = lane%16 and n = 4*(lane/16) + v of each 16x16 block
+    if constexpr (FUSED) {
+        const int nw = n0 + 64 * wn, NC = (N + 63) >> 6;
+        if (nw >= N)
+            return; // no column of this wavefront exists (after the last barrier)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int m = m0 + 128 * wm + 16 * j + (lane & 15);
+            const int label = m < M ? loss.labels[m] : -1;
+            float l[16], mx = -INFINITY;
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int n = nw + 16 * i + 4 * (lane >> 4) + v;
+                    const float logit = (float)(_Float16)acc[i][j][v]; // what the stored fp16 logit would hold
+                    l[4 * i + v] = n < N ? logit : -INFINITY;
+                    mx = fmaxf(mx, l[4 * i + v]);
+                    if (n == label)
+                        loss.label_logit[m] = logit;
+                }
+            float se = 0.f;
+            if (mx != -INFINITY) {
+#pragma unroll
+                for (int e = 0; e < 16; ++e)
+                    se += __expf(l[e] - mx);
+            }
+#pragma unroll
+            for (int o = 16; o <= 32; o <<= 1) { // the four lanes that share a row
+                const float m2 = __shfl_xor(mx, o, 64), s2 = __shfl_xor(se, o, 64);
+                lse_merge(mx, se, m2, s2);
+            }
+            if (lane < 16 && m < M)
+                loss.pairs[(size_t)m * NC + (nw >> 6)] = make_float2(mx, se);
+        }
+        return;
+    }
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
         const int m = m0 + 128 * wm + 16 * j + (lane & 15);
@@ -123,6 +173,31 @@ __global__ __launch_bounds__(512, 2) void dense_kernel(const _Float16 *__restric
     }
 }
 
+// One wavefront per row: merge the row's pairs, then nll = log(sum of exp) - label's logit; a label outside
+// [0, V) gives 0, as in the unfused loss.
+__global__ __launch_bounds__(64) void loss_finish_kernel(LossParts loss, int V, float *__restrict__ nll)
+{
+    const int row = blockIdx.x, lane = threadIdx.x, NC = (V + 63) >> 6;
+    const int label = loss.labels[row];
+    if (label < 0 || label >= V) { // uniform across the wavefront
+        if (lane == 0)
+            nll[row] = 0.f;
+        return;
+    }
+    float mx = -INFINITY, se = 0.f;
+    for (int c = lane; c < NC; c += 64) {
+        const float2 p = loss.pairs[(size_t)row * NC + c];
+        lse_merge(mx, se, p.x, p.y);
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const float m2 = __shfl_xor(mx, o, 64), s2 = __shfl_xor(se, o, 64);
+        lse_merge(mx, se, m2, s2);
+    }
+    if (lane == 0)
+        nll[row] = logf(se) + (mx - loss.label_logit[row]); // difference first: exact for fp16 inputs
+}
+
 } // namespace
 
 // Large tiles pay from about half a tile per CU on (measured: 128 tiles of 2048 x 4096 already run 12 % faster
@@ -134,7 +209,32 @@ int fq_launch_dense_tiled(const void *x, int M, const void *W, int N, int K, voi
 {
     const int total = ((N + DT - 1) / DT) * ((M + DT - 1) / DT);
     dim3 grid(8 * ((total + 7) / 8)), block(512);
-    hipLaunchKernelGGL(dense_kernel, grid, block, 0, st, static_cast<const _Float16 *>(x), M,
-                       static_cast<const _Float16 *>(W), N, K, static_cast<_Float16 *>(out));
+    hipLaunchKernelGGL(dense_kernel<false>, grid, block, 0, st, static_cast<const _Float16 *>(x), M,
+                       static_cast<const _Float16 *>(W), N, K, static_cast<_Float16 *>(out), LossParts{});
+    return (int)hipGetLastError();
+}
+
+size_t fq_head_nll_scratch_bytes(int M, int V)
+{
+    const size_t pairs = (size_t)M * ((V + 63) / 64) * sizeof(float2);
+    return pairs + (size_t)M * sizeof(float);
+}
+
+// workspace: fq_head_nll_scratch_bytes(M, V) bytes, 8-byte aligned.
+int fq_launch_head_nll(const void *x, int M, const void *W, int V, int K, const int32_t *labels, float *nll,
+                       void *workspace, fq_stream st)
+{
+    LossParts loss;
+    loss.labels = labels;
+    loss.pairs = static_cast<float2 *>(workspace);
+    loss.label_logit = reinterpret_cast<float *>(loss.pairs + (size_t)M * ((V + 63) / 64));
+    const int total = ((V + DT - 1) / DT) * ((M + DT - 1) / DT);
+    dim3 grid(8 * ((total + 7) / 8)), block(512);
+    hipLaunchKernelGGL(dense_kernel<true>, grid, block, 0, st, static_cast<const _Float16 *>(x), M,
+                       static_cast<const _Float16 *>(W), V, K, static_cast<_Float16 *>(nullptr), loss);
+    int rc = (int)hipGetLastError();
+    if (rc != 0)
+        return rc;
+    hipLaunchKernelGGL(loss_finish_kernel, dim3(M), dim3(64), 0, st, loss, V, nll);
     return (int)hipGetLastError();
 }

@@ -40,6 +40,10 @@ int fq_launch_dense(const void *x, int M, const void *W, int N, int K, void *out
 // The same product with 256 x 256 tiles, both operands through LDS; pays once its tiles fill the chip.
 bool fq_dense_tiled_pays(int M, int N);
 int fq_launch_dense_tiled(const void *x, int M, const void *W, int N, int K, void *out, fq_stream st);
+// Head GEMM with the token loss in its epilogue; workspace of fq_head_nll_scratch_bytes(M, V) bytes.
+size_t fq_head_nll_scratch_bytes(int M, int V);
+int fq_launch_head_nll(const void *x, int M, const void *W, int V, int K, const int32_t *labels, float *nll,
+                       void *workspace, fq_stream st);
 int fq_launch_glue(int op, const void *a, const void *b, const void *c, int M, int H, void *out, fq_stream st);
 int fq_launch_nll(const void *logits, const int32_t *labels, int M, int V, float *nll, fq_stream st);
 int fq_launch_logit_l2(const void *a, const void *b, int M, int V, float *dist, fq_stream st);

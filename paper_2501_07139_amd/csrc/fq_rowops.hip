@@ -5,6 +5,7 @@
 // bandwidth-bound: one pass over their inputs with 128-bit loads.
 #include "fq_device.h"
 #include "fq_internal.h"
+#include "fq_lse.h"
 
 namespace {
 
@@ -93,18 +94,6 @@ __global__ __launch_bounds__(256) void glue_kernel(const _Float16 *__restrict__ 
 // One workgroup per token row; each thread keeps a running (max, sum of
 // exp(l - max)) over its 16-byte chunks, then the pairs are merged across the
 // wavefront and the workgroup.  The label's logit is read directly.
-__device__ __forceinline__ void lse_merge(float &m, float &s, float m2, float s2)
-{
-    const float mx = fmaxf(m, m2);
-    if (mx == -INFINITY) {
-        m = mx;
-        s = 0.f;
-        return;
-    }
-    s = s * __expf(m - mx) + s2 * __expf(m2 - mx);
-    m = mx;
-}
-
 __global__ __launch_bounds__(256) void nll_kernel(const _Float16 *__restrict__ logits,
                                                   const int32_t *__restrict__ labels, int V,
                                                   float *__restrict__ nll)

@@ -14,8 +14,7 @@ become the current models, each remembering its parent.  A current model already
 nothing; the search ends when the pool is empty.  The output is every surviving path, best first by mean
 perplexity of its members.
 
-All arithmetic of the evaluation runs in the library's kernels (`fq_stack_forward`, `fq_dense_f16`,
-`fq_token_nll`); a candidate differs from its parent in one block, so it is run from that block onwards over
+All arithmetic of the evaluation runs in the library's kernels (`fq_stack_forward`, `fq_head_nll`); a candidate differs from its parent in one block, so it is run from that block onwards over
 the parent's cached block inputs.
 """
 from __future__ import annotations
@@ -138,26 +137,27 @@ class CalibrationEval:
     def __init__(self, stack, head, x, labels):
         import torch
 
-        from . import Stack, fq_stack_workspace_bytes
+        from . import Stack, fq_head_nll_workspace_bytes, fq_stack_workspace_bytes
 
         self.stack, self.head, self.x, self.labels = stack, head, x, labels
         self.L = stack.L
         self.one = [Stack([stack.layers[l]]) for l in range(self.L)]
         M = x.shape[0]
         self.ws = torch.empty(fq_stack_workspace_bytes(M, stack.hidden, stack.ffn), dtype=torch.uint8, device=x.device)
+        self.ws_head = torch.empty(fq_head_nll_workspace_bytes(M, head.shape[0]), dtype=torch.uint8, device=x.device)
         self.evaluations = 0
         self.blocks_run = 0
 
     def __call__(self, bitvec: BitVec, parent: Optional[Node], entry: Optional[int]):
-        from . import fq_dense_f16, fq_stack_forward, fq_token_nll
+        from . import fq_head_nll, fq_stack_forward
 
         bv = np.asarray(bitvec, dtype=np.uint8)
         first = 0 if parent is None or parent.state is None else entry // 7
         inputs = [self.x] if first == 0 else list(parent.state[:first + 1])
         for l in range(first, self.L):
             inputs.append(fq_stack_forward(self.one[l], bv[7 * l:7 * l + 7], inputs[l], workspace=self.ws))
-        logits = fq_dense_f16(inputs[self.L], self.head)
-        nll = fq_token_nll(logits, self.labels).cpu().numpy().astype(np.float64)
+        nll = fq_head_nll(inputs[self.L], self.head, self.labels, workspace=self.ws_head)
+        nll = nll.cpu().numpy().astype(np.float64)
         self.evaluations += 1
         self.blocks_run += self.L - first
         return float(np.exp(nll.mean())), inputs

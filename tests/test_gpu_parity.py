@@ -230,6 +230,34 @@ def test_token_nll_against_oracle(fq, torch, shape):
     assert abs(math.exp(got.mean()) / oracle.perplexity(want) - 1) <= 1e-3
 
 
+@pytest.mark.parametrize("case", [(2048, 32000, 512), (2048, 32000, 4096), (300, 1001, 256), (5, 70, 128)], ids=str)
+def test_head_nll_fused_against_oracle(fq, torch, case):
+    """Head GEMM with the loss in its epilogue against the oracle's chain dense -> fp16 logits -> NLL (on a
+    sample of rows where the full product is too slow for the oracle), and against the library's own two
+    calls, which it must reproduce up to the order of the fp32 merges."""
+    M, V, K = case
+    X = fq_synth.activations(51, M, K)
+    W = fq_synth.weights(52, V, K, 0.02 if K > 1024 else 0.05, 99).astype(np.float16)
+    lab = fq_synth.labels(53, M, V)
+    lab[0], lab[-1] = 0, V - 1
+    if M > 4:
+        lab[2] = -1          # ignored position
+        lab[3] = V           # out of range counts as ignored too
+    dX, dW, dl = dev(torch, X), dev(torch, W), dev(torch, lab)
+    got = fq.fq_head_nll(dX, dW, dl).cpu().numpy().astype(np.float64)
+    two = fq.fq_token_nll(fq.fq_dense_f16(dX, dW), dl).cpu().numpy().astype(np.float64)
+    assert np.max(np.abs(got - two)) <= 2e-5
+    rows = np.arange(M)
+    if M * V * K > 1 << 30:
+        rng = np.random.default_rng(1)
+        rows = np.unique(np.concatenate([rng.integers(0, M, 24 if K <= 512 else 6), [0, 2, 3, 255, 256, M - 1]]))
+    want = oracle.token_nll(oracle.round_f16(oracle.dense_f16(X[rows], W)), lab[rows])
+    assert np.max(np.abs(got[rows] - want)) <= 2e-3
+    assert abs(got[rows].mean() - want.mean()) <= 1e-3
+    if M > 4:
+        assert got[2] == 0.0 and got[3] == 0.0
+
+
 # ---------------------------------------------------------------------- glue
 @pytest.mark.parametrize("shape", [(2048, 32000), (130, 1001), (7, 8), (3, 32768)])
 def test_logit_l2_against_oracle(fq, torch, shape):

@@ -109,6 +109,13 @@ def test_error_codes_without_launching_anything():
     assert lib.fq_logit_l2(None, 16, 1, 1, 16, None) == -1
     assert lib.fq_logit_l2(16, 16, 0, 8, 16, None) == -2
     assert lib.fq_logit_l2(16, 24, 1, 8, 16, None) == -5
+    assert lib.fq_head_nll(None, 1, 16, 8, 128, 16, 16, 16, 1 << 20, None) == -1
+    assert lib.fq_head_nll(16, 1, 16, 8, 100, 16, 16, 16, 1 << 20, None) == -2
+    assert lib.fq_head_nll(16, 4, 16, 70, 128, 16, 16, 16, 8, None) == -6 and "need" in fq.fq_last_error()
+    assert lib.fq_head_nll(16, 4, 16, 70, 128, 16, 16, None, 1 << 20, None) == -6
+    assert lib.fq_head_nll(16, 4, 24, 70, 128, 16, 16, 16, 1 << 20, None) == -5
+    assert fq.fq_head_nll_workspace_bytes(4, 70) == 4 * 2 * 8 + 4 * 4 and fq.fq_head_nll_workspace_bytes(0, 70) == 0
+    assert fq.fq_head_nll_workspace_bytes(3, 64) % 16 == 0
     assert lib.fq_glue(9, 16, 16, 16, 1, 128, 16, None) == -2
     assert lib.fq_dense_f16(16, 1, 16, 1, 100, 16, None) == -2
     # the matrix-core kernels address their arrays through 32-bit offsets: 4 GiB of activations is refused
