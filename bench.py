@@ -42,7 +42,7 @@ SEED = 1
 # WRITE_SIZE, KiB per dispatch) scaled by what the same counters read for a 64 MiB device copy (FETCH_SIZE
 # reads 0.500 of the true bytes on this machine, WRITE_SIZE 1.000).  Valid only for the kernel sources whose
 # digest is recorded with it; bench.py reports null once they have changed.
-GEMM_TRAFFIC = {"kernel_digest": "c9a695e7dca03a20", "fetch_bytes": 804.4e6, "write_bytes": 174.2e6}  # profiles/qgemm_gemv_llama2-7b-block_hbm_traffic.txt
+GEMM_TRAFFIC = {"kernel_digest": "c9a695e7dca03a20", "fetch_bytes": 804.8e6, "write_bytes": 174.2e6}  # profiles/qgemm_gemv_llama2-7b-block_hbm_traffic.txt
 
 
 def kernel_digest() -> str:
@@ -63,7 +63,7 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
     ap.add_argument("--cpu-rows", type=int, default=96, help="rows of leg A the oracle is timed on")
     ap.add_argument("--single-launches", action="store_true",
-                    help="for counter runs: a 64 MiB device copy, then one launch of each linear at M=2048 and M=1, no timing")
+                    help="for counter runs: a 64 MiB device copy, then one launch of each linear at M=2048 and M=1 and one of the head with fused loss, no timing")
     return ap.parse_args()
 
 
@@ -152,8 +152,10 @@ def main():
             torch.cuda.synchronize()
             fq.fq_qlinear((mm if K == FFN else u)[:1].contiguous(), w)
             torch.cuda.synchronize()
+        fq.fq_head_nll(u, head, labels, out=nll, workspace=ws_head)
+        torch.cuda.synchronize()
         print("single launches done: copy, then (M=2048, M=1) for " + ", ".join(
-            "%s %d-bit" % (fq_synth.MATRIX_NAMES[j], int(bitvec[j])) for j in range(7)))
+            "%s %d-bit" % (fq_synth.MATRIX_NAMES[j], int(bitvec[j])) for j in range(7)) + ", then head with fused loss")
         return
 
     # ------------------------------------------------------- algorithmic work
