@@ -45,6 +45,9 @@ SEED = 1
 GEMM_TRAFFIC = {"kernel_digest": "c9a695e7dca03a20", "fetch_bytes": 804.8e6, "write_bytes": 174.2e6}  # profiles/qgemm_gemv_llama2-7b-block_hbm_traffic.txt
 
 
+SWAP_ENTRY = 4  # the matrix (gate) the transition leg swaps
+
+
 def kernel_digest() -> str:
     import hashlib
 
@@ -99,6 +102,9 @@ def main():
         codes, s, z = fq.fq_quantize_rtn(W, b)
         host_q.append((codes, s, z))
         block.append({b: fq.PackedMatrix.from_host(codes, s, z, b)})
+        if j == SWAP_ENTRY:  # a second stored width of one matrix, for the transition leg
+            swap_bits = 2 if b != 2 else 4
+            swap_q = fq.fq_quantize_rtn(W, swap_bits)
         del W
     # decode leg: DECODE_LAYERS distinct device copies of the block
     dec_layers = [block]
@@ -202,6 +208,29 @@ def main():
     l2 = torch.empty(M_FWD, dtype=torch.float32, device=dev)
     ms_l2 = timed(lambda: fq.fq_logit_l2(logits, logits_b, out=l2), reps)
 
+    # beyond the step: a run-time transition, one matrix swapped for its other stored width and back.  The new
+    # packing comes from pinned host memory, so this is a PCIe figure.
+    from paper_2501_07139_amd import elastic
+
+    store = elastic.HostStore([[{int(bitvec[j]): host_q[j], **({swap_bits: swap_q} if j == SWAP_ENTRY else {})}
+                                for j in range(7)]])
+    members = [tuple(int(b) for b in bitvec), tuple(swap_bits if j == SWAP_ENTRY else int(b) for j, b in enumerate(bitvec))]
+    members.sort(key=lambda v: -v[SWAP_ENTRY])
+    hosted = elastic.ElasticModel(store, members)
+    for _ in range(2):  # first use: allocations
+        hosted.move_to(1)
+        hosted.move_to(0)
+    torch.cuda.synchronize()
+    loaded0, t0 = hosted.bytes_loaded, time.perf_counter()
+    for _ in range(5):
+        hosted.move_to(1)
+        hosted.move_to(0)
+    torch.cuda.synchronize()
+    swap_s = (time.perf_counter() - t0) / 10
+    swap_bytes = (hosted.bytes_loaded - loaded0) / 10
+    ms_dec_hosted = timed(lambda: hosted.forward(x_dec), reps)
+    del hosted, store
+
     # the dominant kernel: dequant-GEMM launches of leg A, one by one
     kernels = []
     u = fq.fq_glue(0, x_fwd)
@@ -273,6 +302,10 @@ def main():
                                            "max_abs_diff_to_fused": float((nll_two - nll).abs().max().item())},
             "logit_l2_outside_the_step": {"GBps": round(2 * nll_bytes / ms_l2 / 1e6, 1), "ms": round(ms_l2, 4),
                                           "frac_hbm_peak": round(2 * nll_bytes / ms_l2 / 1e6 / PEAK_HBM_GBPS, 4)},
+            "transition_outside_the_step": {"matrix": fq_synth.MATRIX_NAMES[SWAP_ENTRY], "widths": [int(bitvec[SWAP_ENTRY]), swap_bits],
+                                            "ms_per_swap": round(swap_s * 1e3, 3), "MB_loaded_per_swap": round(swap_bytes / 1e6, 2),
+                                            "GBps_host_to_device": round(swap_bytes / swap_s / 1e9, 1),
+                                            "ms_block_decode_of_hosted_model": round(ms_dec_hosted, 4)},
             "gemv_m1": {"GBps_single_launches": round(block_bytes / gemv_ms_total / 1e6, 1),
                         "GBps_stack_decode": round(gemv_bytes / ms_dec / 1e6, 1),
                         "ms_stack_decode": round(ms_dec, 4), "layers": DECODE_LAYERS,
