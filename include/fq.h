@@ -219,6 +219,42 @@ int fq_head_nll(const void *x, int M, const void *W, int V, int K, const int32_t
  */
 int fq_logit_l2(const void *a, const void *b, int M, int V, float *dist_out, void *stream);
 
+/*
+ * Real decoder blocks around the quantized linears, one decode step (the hosted
+ * models of Section "Experiment" are Llama decoders; Section "Introduction":
+ * served one token at a time).  Per block, for the token at position pos:
+ *   u = rms(x); q,k,v = L(u); q' = rope(q,pos), k' = rope(k,pos);
+ *   K[pos] = k', V[pos] = v; a = softmax_t(q'.K[t]/sqrt(128)).V[t], t <= pos, per head;
+ *   o = Lo(a); x1 = x + o; u2 = rms(x1); g,p = Lgate(u2),Lup(u2);
+ *   d = Ldown(silu(g)*p); x_next = x1 + d.
+ * rms(t) = t/sqrt(mean(t^2)+1e-5) without gain (a model's norm gains are folded
+ * into the following linears before quantization); rope rotates the adjacent
+ * pair (2i, 2i+1) of every head by the angle whose (cos, sin) the table gives;
+ * heads are 128 wide, as many key/value heads as query heads; every named tensor
+ * is stored as fp16.
+ *
+ * fq_attn_decode: the attention step alone.  q, k, v fp16 [H] (H = 128 n_heads),
+ * device, read.  k_cache, v_cache fp16 [Tmax,H], device: rows < pos read, row pos
+ * written.  rope fp32 [Tmax][64][2] = (cos, sin) of pos * theta_i, device, read.
+ * out fp16 [H], device, written.  workspace: device scratch of at least
+ * fq_attn_workspace_bytes(Tmax, n_heads) bytes, 16-byte aligned, owned by the
+ * caller.  FQ_ERR_SHAPE unless 0 <= pos < Tmax.
+ *
+ * fq_decode_step: L blocks.  layers/bitvec as in fq_stack_forward.  x_in, x_out
+ * fp16 [hidden], device.  k_cache, v_cache fp16 [L,Tmax,hidden], device, layer l
+ * at offset l*Tmax*hidden.  workspace of fq_decode_workspace_bytes(hidden, ffn,
+ * Tmax) bytes, 16-byte aligned.  Six launches per block (q/k/v, attention and
+ * its merge when pos >= 128, o, gate/up, down), all on `stream`; positions must
+ * be fed in order 0, 1, 2, ... for the cache to be complete.
+ */
+size_t fq_attn_workspace_bytes(int Tmax, int n_heads);
+size_t fq_decode_workspace_bytes(int hidden, int ffn, int Tmax);
+int fq_attn_decode(const void *q, const void *k, const void *v, void *k_cache, void *v_cache, int pos, int Tmax,
+                   int n_heads, const float *rope, void *out, void *workspace, size_t workspace_bytes, void *stream);
+int fq_decode_step(const fq_layer *layers, int L, const uint8_t *bitvec, const void *x_in, void *x_out,
+                   void *k_cache, void *v_cache, int pos, int Tmax, const float *rope, void *workspace,
+                   size_t workspace_bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

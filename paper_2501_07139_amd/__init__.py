@@ -66,6 +66,10 @@ def _load() -> ctypes.CDLL:
         "fq_logit_l2": (ci, [vp, vp, ci, ci, vp, vp]),
         "fq_head_nll_workspace_bytes": (sz, [ci, ci]),
         "fq_head_nll": (ci, [vp, ci, vp, ci, ci, vp, vp, vp, sz, vp]),
+        "fq_attn_workspace_bytes": (sz, [ci, ci]),
+        "fq_decode_workspace_bytes": (sz, [ci, ci, ci]),
+        "fq_attn_decode": (ci, [vp, vp, vp, vp, vp, ci, ci, ci, vp, vp, vp, sz, vp]),
+        "fq_decode_step": (ci, [ctypes.POINTER(fq_layer), ci, vp, vp, vp, vp, vp, ci, ci, vp, vp, sz, vp]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -77,7 +81,8 @@ def _load() -> ctypes.CDLL:
 _lib = _load()
 EXPORTS = ("fq_last_error", "fq_version", "fq_quantize_rtn", "fq_packed_bytes", "fq_meta_count", "fq_pack_groups",
            "fq_dequant", "fq_qlinear", "fq_stack_workspace_bytes", "fq_stack_forward", "fq_glue", "fq_dense_f16",
-           "fq_token_nll", "fq_logit_l2", "fq_head_nll_workspace_bytes", "fq_head_nll")
+           "fq_token_nll", "fq_logit_l2", "fq_head_nll_workspace_bytes", "fq_head_nll",
+           "fq_attn_workspace_bytes", "fq_decode_workspace_bytes", "fq_attn_decode", "fq_decode_step")
 
 
 def _check(rc: int) -> None:
@@ -321,4 +326,63 @@ def fq_token_nll(logits, labels, out=None, stream=None):
     if out is None:
         out = torch.empty(M, dtype=torch.float32, device=logits.device)
     _check(_lib.fq_token_nll(_dp(logits), _dp(labels), M, V, _dp(out), _stream(stream)))
+    return out
+
+
+# ------------------------------------------------------------ real decoder blocks
+def rope_table(Tmax: int, head_dim: int = 128, base: float = 10000.0, device="cuda"):
+    """(cos, sin) of pos * base^(-2i/head_dim) as fp32 [Tmax, head_dim/2, 2] on the device (computed in
+    fp64 on the host, rounded once)."""
+    torch = _torch()
+    ang = np.arange(Tmax, dtype=np.float64)[:, None] * base ** (-2.0 * np.arange(head_dim // 2, dtype=np.float64) / head_dim)
+    return torch.from_numpy(np.stack([np.cos(ang), np.sin(ang)], axis=-1).astype(np.float32)).to(device)
+
+
+def fq_attn_workspace_bytes(Tmax: int, n_heads: int) -> int:
+    return _lib.fq_attn_workspace_bytes(Tmax, n_heads)
+
+
+def fq_decode_workspace_bytes(hidden: int, ffn: int, Tmax: int) -> int:
+    return _lib.fq_decode_workspace_bytes(hidden, ffn, Tmax)
+
+
+def fq_attn_decode(q, k, v, k_cache, v_cache, pos: int, rope, out=None, workspace=None, stream=None):
+    torch = _torch()
+    q, k, v = (_dev(t, torch.float16, n) for t, n in ((q, "q"), (k, "k"), (v, "v")))
+    k_cache, v_cache = _dev(k_cache, torch.float16, "k_cache"), _dev(v_cache, torch.float16, "v_cache")
+    rope = _dev(rope, torch.float32, "rope")
+    Tmax, H = k_cache.shape
+    if q.numel() != H or k.numel() != H or v.numel() != H or v_cache.shape != k_cache.shape or H % 128:
+        raise ValueError("fq_attn_decode: q, k, v [H], caches [Tmax,H], H a multiple of 128")
+    if rope.shape[0] < Tmax or tuple(rope.shape[1:]) != (64, 2):
+        raise ValueError("fq_attn_decode: rope must be [>=Tmax, 64, 2]")
+    if out is None:
+        out = torch.empty_like(q)
+    if workspace is None:
+        workspace = torch.empty(fq_attn_workspace_bytes(Tmax, H // 128), dtype=torch.uint8, device=q.device)
+    _check(_lib.fq_attn_decode(_dp(q), _dp(k), _dp(v), _dp(k_cache), _dp(v_cache), pos, Tmax, H // 128, _dp(rope),
+                               _dp(out), _dp(workspace), workspace.numel(), _stream(stream)))
+    return out
+
+
+def fq_decode_step(stack: Stack, bitvec, x, k_cache, v_cache, pos: int, rope, out=None, workspace=None, stream=None):
+    """One token through the stack's blocks as real decoder blocks; caches fp16 [L,Tmax,hidden]."""
+    torch = _torch()
+    x = _dev(x, torch.float16, "x")
+    k_cache, v_cache = _dev(k_cache, torch.float16, "k_cache"), _dev(v_cache, torch.float16, "v_cache")
+    rope = _dev(rope, torch.float32, "rope")
+    bitvec = np.ascontiguousarray(bitvec, dtype=np.uint8)
+    if bitvec.size != 7 * stack.L:
+        raise ValueError("bitvec needs 7 entries per block")
+    L, Tmax, H = k_cache.shape
+    if L != stack.L or H != stack.hidden or v_cache.shape != k_cache.shape or x.numel() != H:
+        raise ValueError("fq_decode_step: x [hidden], caches [L,Tmax,hidden]")
+    if rope.shape[0] < Tmax or tuple(rope.shape[1:]) != (64, 2):
+        raise ValueError("fq_decode_step: rope must be [>=Tmax, 64, 2]")
+    if out is None:
+        out = torch.empty_like(x)
+    if workspace is None:
+        workspace = torch.empty(fq_decode_workspace_bytes(H, stack.ffn, Tmax), dtype=torch.uint8, device=x.device)
+    _check(_lib.fq_decode_step(stack.table, stack.L, _hp(bitvec), _dp(x), _dp(out), _dp(k_cache), _dp(v_cache), pos,
+                               Tmax, _dp(rope), _dp(workspace), workspace.numel(), _stream(stream)))
     return out

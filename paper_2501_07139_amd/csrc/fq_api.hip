@@ -157,6 +157,33 @@ extern "C" int fq_logit_l2(const void *a, const void *b, int M, int V, float *di
     return check_hip(fq_launch_logit_l2(a, b, M, V, dist_out, static_cast<fq_stream>(stream)), "fq_logit_l2 launch");
 }
 
+// Shapes of the block's seven matrices and the selected packing of each, checked before anything is launched.
+static int validate_layers(const char *fn, const fq_layer *layers, int L, const uint8_t *bitvec, int *H_out, int *F_out)
+{
+    const int H = layers[0].m[0].K, F = layers[0].m[4].N;
+    if (H <= 0 || F <= 0 || H % 128 != 0 || F % 128 != 0 || H > kMaxGlueH || F > kMaxGlueH)
+        return fq_fail(FQ_ERR_SHAPE, "%s: hidden=%d ffn=%d must be multiples of 128, at most %d", fn, H, F, kMaxGlueH);
+    for (int l = 0; l < L; ++l)
+        for (int j = 0; j < 7; ++j) {
+            const fq_matrix &mx = layers[l].m[j];
+            const int wantN = (j == 4 || j == 5) ? F : H, wantK = (j == 6) ? F : H;
+            if (mx.N != wantN || mx.K != wantK)
+                return fq_fail(FQ_ERR_SHAPE, "%s: layer %d matrix %d is %dx%d, expected %dx%d", fn, l, j, mx.N, mx.K,
+                               wantN, wantK);
+            const int bi = fq_bits_index(bitvec[7 * l + j]);
+            if (bi < 0)
+                return fq_fail(FQ_ERR_BITS, "%s: bitvec[%d]=%d not in {2,3,4,8}", fn, 7 * l + j, (int)bitvec[7 * l + j]);
+            if (!mx.packed[bi] || !mx.scales[bi] || !mx.zeros[bi])
+                return fq_fail(FQ_ERR_NULL, "%s: layer %d matrix %d has no %d-bit packing", fn, l, j,
+                               (int)bitvec[7 * l + j]);
+            if (!aligned16(mx.packed[bi]) || !aligned16(mx.scales[bi]) || !aligned16(mx.zeros[bi]))
+                return fq_fail(FQ_ERR_ALIGN, "%s: layer %d matrix %d is not 16-byte aligned", fn, l, j);
+        }
+    *H_out = H;
+    *F_out = F;
+    return FQ_OK;
+}
+
 // Workspace: u, q, k, v, a, o, x1, u2, d, xcur (hidden wide) and g, p, m (ffn wide).
 extern "C" size_t fq_stack_workspace_bytes(int M, int hidden, int ffn)
 {
@@ -173,29 +200,10 @@ extern "C" int fq_stack_forward(const fq_layer *layers, int L, const uint8_t *bi
         return fq_fail(FQ_ERR_NULL, "fq_stack_forward: NULL argument");
     if (L <= 0 || M <= 0)
         return fq_fail(FQ_ERR_SHAPE, "fq_stack_forward: L=%d M=%d", L, M);
-    const int H = layers[0].m[0].K, F = layers[0].m[4].N;
-    if (H <= 0 || F <= 0 || H % 128 != 0 || F % 128 != 0 || H > kMaxGlueH || F > kMaxGlueH)
-        return fq_fail(FQ_ERR_SHAPE, "fq_stack_forward: hidden=%d ffn=%d must be multiples of 128, at most %d", H, F,
-                       kMaxGlueH);
-    // validate every selected packing before anything is launched
+    int H = 0, F = 0;
+    if (int rc = validate_layers("fq_stack_forward", layers, L, bitvec, &H, &F))
+        return rc;
     fq_packed_ref sel[7];
-    for (int l = 0; l < L; ++l)
-        for (int j = 0; j < 7; ++j) {
-            const fq_matrix &mx = layers[l].m[j];
-            const int wantN = (j == 4 || j == 5) ? F : H, wantK = (j == 6) ? F : H;
-            if (mx.N != wantN || mx.K != wantK)
-                return fq_fail(FQ_ERR_SHAPE, "fq_stack_forward: layer %d matrix %d is %dx%d, expected %dx%d", l, j,
-                               mx.N, mx.K, wantN, wantK);
-            const int bi = fq_bits_index(bitvec[7 * l + j]);
-            if (bi < 0)
-                return fq_fail(FQ_ERR_BITS, "fq_stack_forward: bitvec[%d]=%d not in {2,3,4,8}", 7 * l + j,
-                               (int)bitvec[7 * l + j]);
-            if (!mx.packed[bi] || !mx.scales[bi] || !mx.zeros[bi])
-                return fq_fail(FQ_ERR_NULL, "fq_stack_forward: layer %d matrix %d has no %d-bit packing", l, j,
-                               (int)bitvec[7 * l + j]);
-            if (!aligned16(mx.packed[bi]) || !aligned16(mx.scales[bi]) || !aligned16(mx.zeros[bi]))
-                return fq_fail(FQ_ERR_ALIGN, "fq_stack_forward: layer %d matrix %d is not 16-byte aligned", l, j);
-        }
     if (workspace_bytes < fq_stack_workspace_bytes(M, H, F))
         return fq_fail(FQ_ERR_WORKSPACE, "fq_stack_forward: workspace of %zu bytes, need %zu", workspace_bytes,
                        fq_stack_workspace_bytes(M, H, F));
@@ -263,4 +271,100 @@ extern "C" int fq_stack_forward(const fq_layer *layers, int L, const uint8_t *bi
         xcur = xnext;
     }
     return FQ_OK;
+}
+
+// Workspace: q, k, v, a, o, x1, d, x (hidden wide), g, p (ffn wide), then the attention's split results.
+extern "C" size_t fq_decode_workspace_bytes(int hidden, int ffn, int Tmax)
+{
+    if (hidden <= 0 || ffn <= 0 || Tmax <= 0 || hidden % 128 != 0)
+        return 0;
+    return 8 * align_up((size_t)hidden * 2) + 2 * align_up((size_t)ffn * 2) + align_up(fq_attn_scratch_bytes(Tmax, hidden / 128));
+}
+
+extern "C" size_t fq_attn_workspace_bytes(int Tmax, int n_heads)
+{
+    if (Tmax <= 0 || n_heads <= 0)
+        return 0;
+    return align_up(fq_attn_scratch_bytes(Tmax, n_heads));
+}
+
+extern "C" int fq_attn_decode(const void *q, const void *k, const void *v, void *k_cache, void *v_cache, int pos,
+                              int Tmax, int n_heads, const float *rope, void *out, void *workspace,
+                              size_t workspace_bytes, void *stream)
+{
+    if (!q || !k || !v || !k_cache || !v_cache || !rope || !out || !workspace)
+        return fq_fail(FQ_ERR_NULL, "fq_attn_decode: NULL argument");
+    if (n_heads <= 0 || Tmax <= 0 || pos < 0 || pos >= Tmax)
+        return fq_fail(FQ_ERR_SHAPE, "fq_attn_decode: n_heads=%d Tmax=%d pos=%d (need 0 <= pos < Tmax)", n_heads, Tmax, pos);
+    if (workspace_bytes < fq_attn_scratch_bytes(Tmax, n_heads))
+        return fq_fail(FQ_ERR_WORKSPACE, "fq_attn_decode: workspace of %zu bytes, need %zu", workspace_bytes,
+                       fq_attn_scratch_bytes(Tmax, n_heads));
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(k_cache) || !aligned16(v_cache) ||
+        !aligned16(rope) || !aligned16(out) || !aligned16(workspace))
+        return fq_fail(FQ_ERR_ALIGN, "fq_attn_decode: pointers must be 16-byte aligned");
+    return check_hip(fq_launch_attn_decode(q, k, v, k_cache, v_cache, pos, n_heads, rope, out, workspace,
+                                           static_cast<fq_stream>(stream)), "fq_attn_decode launch");
+}
+
+extern "C" int fq_decode_step(const fq_layer *layers, int L, const uint8_t *bitvec, const void *x_in, void *x_out,
+                              void *k_cache, void *v_cache, int pos, int Tmax, const float *rope, void *workspace,
+                              size_t workspace_bytes, void *stream)
+{
+    if (!layers || !bitvec || !x_in || !x_out || !k_cache || !v_cache || !rope || !workspace)
+        return fq_fail(FQ_ERR_NULL, "fq_decode_step: NULL argument");
+    if (L <= 0 || Tmax <= 0 || pos < 0 || pos >= Tmax)
+        return fq_fail(FQ_ERR_SHAPE, "fq_decode_step: L=%d Tmax=%d pos=%d (need 0 <= pos < Tmax)", L, Tmax, pos);
+    int H = 0, F = 0;
+    if (int rc = validate_layers("fq_decode_step", layers, L, bitvec, &H, &F))
+        return rc;
+    for (int l = 0; l < L; ++l)
+        for (int j = 0; j < 7; ++j)
+            if (!fq_gemv_can_stream(1, layers[l].m[j].K, bitvec[7 * l + j], 2))
+                return fq_fail(FQ_ERR_SHAPE, "fq_decode_step: rows of %d elements do not fit the decode kernel",
+                               layers[l].m[j].K);
+    if (workspace_bytes < fq_decode_workspace_bytes(H, F, Tmax))
+        return fq_fail(FQ_ERR_WORKSPACE, "fq_decode_step: workspace of %zu bytes, need %zu", workspace_bytes,
+                       fq_decode_workspace_bytes(H, F, Tmax));
+    if (!aligned16(x_in) || !aligned16(x_out) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(rope) ||
+        !aligned16(workspace))
+        return fq_fail(FQ_ERR_ALIGN, "fq_decode_step: pointers must be 16-byte aligned");
+
+    fq_stream st = static_cast<fq_stream>(stream);
+    const int n_heads = H / 128;
+    const size_t hb = align_up((size_t)H * 2), fb = align_up((size_t)F * 2), layer_cache = (size_t)Tmax * H * 2;
+    char *ws = static_cast<char *>(workspace);
+    void *q = ws, *k = ws + hb, *v = ws + 2 * hb, *a = ws + 3 * hb, *o = ws + 4 * hb, *x1 = ws + 5 * hb,
+         *d = ws + 6 * hb, *xc = ws + 7 * hb, *g = ws + 8 * hb, *p = ws + 8 * hb + fb, *attn = ws + 8 * hb + 2 * fb;
+    fq_packed_ref sel[7];
+    const void *xres = x_in;
+    for (int l = 0; l < L; ++l) {
+        for (int j = 0; j < 7; ++j) {
+            const fq_matrix &mx = layers[l].m[j];
+            const int bits = bitvec[7 * l + j], bi = fq_bits_index(bits);
+            sel[j] = fq_packed_ref{mx.packed[bi], mx.scales[bi], mx.zeros[bi], mx.N, mx.K, bits};
+        }
+        void *const qkv[3] = {q, k, v};
+        void *const gp[2] = {g, p};
+        int rc;
+#define FQ_STEP(call) \
+    if ((rc = (call)) != FQ_OK) \
+        return rc
+        // the previous block's output x1 + d is formed (into xc) by this block's first launch
+        const fq_gemv_input in_qkv = (l == 0) ? fq_gemv_input{x_in, nullptr, nullptr, nullptr, 1}
+                                              : fq_gemv_input{x1, d, nullptr, xc, 3};
+        if (l > 0)
+            xres = xc;
+        FQ_STEP(check_hip(fq_launch_gemv_multi(in_qkv, 1, &sel[0], qkv, 3, st), "decode q/k/v"));
+        FQ_STEP(check_hip(fq_launch_attn_decode(q, k, v, static_cast<char *>(k_cache) + l * layer_cache,
+                                                static_cast<char *>(v_cache) + l * layer_cache, pos, n_heads, rope, a,
+                                                attn, st), "decode attention"));
+        FQ_STEP(check_hip(fq_launch_gemv_multi(fq_gemv_input{a, nullptr, nullptr, nullptr, 0}, 1, &sel[3], &o, 1, st),
+                          "decode o"));
+        FQ_STEP(check_hip(fq_launch_gemv_multi(fq_gemv_input{xres, o, nullptr, x1, 3}, 1, &sel[4], gp, 2, st),
+                          "decode gate/up"));
+        FQ_STEP(check_hip(fq_launch_gemv_multi(fq_gemv_input{g, p, nullptr, nullptr, 6}, 1, &sel[6], &d, 1, st),
+                          "decode down"));
+#undef FQ_STEP
+    }
+    return check_hip(fq_launch_glue(2, x1, d, nullptr, 1, H, x_out, st), "glue add");
 }

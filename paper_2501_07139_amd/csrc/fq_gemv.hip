@@ -155,6 +155,7 @@ struct GemvJobs {
 // the block stores an fp16 tensor):
 //   0: x = a                      1: x = rms(a)                 2: x = rms(a + b + c)
 //   3: aux = a + b, x = rms(aux)  4: x = rms(silu(a) * b)       5: aux = rms(a + b), x = rms(aux)
+//   6: x = silu(a) * b (no norm: the MLP of a real decoder block)
 // aux (fp16 [M,K]) is written by workgroup 0 only.
 struct GemvInput {
     const _Float16 *a, *b, *c;
@@ -264,7 +265,7 @@ __device__ __forceinline__ void gemv_combine(const h8 (&r)[GemvInputs<MODE>::N],
             float t = (float)r[0][e];
             if constexpr (MODE == 2)
                 t = t + (float)r[1][e] + (float)r[2][e];
-            else if constexpr (MODE == 4)
+            else if constexpr (MODE == 4 || MODE == 6)
                 t = t * __builtin_amdgcn_rcpf(1.0f + __expf(-t)) * (float)r[1][e]; // reciprocal good to 1 ulp
             else
                 t = t + (float)r[1][e];
@@ -476,7 +477,7 @@ __device__ __forceinline__ void gemv_body(const GemvJob job, int bj, const GemvI
         if (has0)
             fetch(0, v0, true);
         float inv1 = 1.0f, inv2 = 1.0f;
-        if constexpr (MODE != 0) {
+        if constexpr (MODE != 0 && MODE != 6) {
             // sum of squares of the row; second: of the fp16 result of the first rms
             auto squares = [&](bool second) {
                 float ss = 0.f;
@@ -706,10 +707,11 @@ typedef void (*GemvKernel)(GemvInput, int, int, GemvJobs);
 // One kernel per input mode, for a single activation row and for up to sixteen.
 GemvKernel gemv_kernel_for(int mode, int M, int *slot)
 {
-    static const GemvKernel table[6][2] = {
+    static const GemvKernel table[7][2] = {
         {gemv_stream_kernel<0, 1>, gemv_stream_kernel<0, 4>}, {gemv_stream_kernel<1, 1>, gemv_stream_kernel<1, 4>},
         {gemv_stream_kernel<2, 1>, gemv_stream_kernel<2, 4>}, {gemv_stream_kernel<3, 1>, gemv_stream_kernel<3, 4>},
         {gemv_stream_kernel<4, 1>, gemv_stream_kernel<4, 4>}, {gemv_stream_kernel<5, 1>, gemv_stream_kernel<5, 4>},
+        {gemv_stream_kernel<6, 1>, gemv_stream_kernel<6, 4>},
     };
     const int wide = M == 1 ? 0 : 1;
     *slot = 2 * mode + wide;
@@ -736,7 +738,7 @@ int rows_per_supertile(int bits) { return bits == 2 ? 32 : (bits == 3 ? 64 : 16)
 int gemv_resident_blocks(GemvKernel kernel, int slot, size_t lds, int *out)
 {
     static int cus = 0;
-    static bool prepared[12];
+    static bool prepared[14];
     if (cus == 0) {
         int dev = 0, n = 0;
         hipError_t e = hipGetDevice(&dev);
@@ -755,8 +757,8 @@ int gemv_resident_blocks(GemvKernel kernel, int slot, size_t lds, int *out)
         prepared[slot] = true;
     }
     // the answer depends only on the kernel and the LDS request: remember the last few
-    static size_t seen_lds[12][4];
-    static int seen_blocks[12][4], seen[12];
+    static size_t seen_lds[14][4];
+    static int seen_blocks[14][4], seen[14];
     for (int i = 0; i < seen[slot]; ++i)
         if (seen_lds[slot][i] == lds) {
             *out = seen_blocks[slot][i];
@@ -785,7 +787,7 @@ bool fq_gemv_can_stream(int M, int K, int bits, int inputs)
 int fq_launch_gemv_multi(const fq_gemv_input &src, int M, const fq_packed_ref *w, void *const *outs, int count,
                          fq_stream st)
 {
-    if (src.mode < 0 || src.mode > 5)
+    if (src.mode < 0 || src.mode > 6)
         return (int)hipErrorInvalidValue;
     const int inputs = src.mode == 2 ? 3 : (src.mode >= 3 ? 2 : 1);
     GemvJobs jobs;

@@ -26,12 +26,13 @@ int fq_launch_gemv(const void *x, int M, const fq_packed_ref &w, void *out, fq_s
 // Streaming decode kernel: up to three matrices that share their input and K in one launch (M <= 16).
 // The input is x = f(a, b, c), fp16 [M,K] each, with the block's row-wise glue folded in:
 //   mode 0: a   1: rms(a)   2: rms(a+b+c)   3: aux = a+b, rms(aux)   4: rms(silu(a)*b)   5: aux = rms(a+b), rms(aux)
+//   mode 6: silu(a)*b
 struct fq_gemv_input {
     const void *a, *b, *c;
     void *aux;
     int mode;
 };
-// inputs: how many of a, b, c the mode reads (mode 2: three, modes 3 to 5: two, else one)
+// inputs: how many of a, b, c the mode reads (mode 2: three, modes 3 to 6: two, else one)
 bool fq_gemv_can_stream(int M, int K, int bits, int inputs);
 int fq_launch_gemv_multi(const fq_gemv_input &src, int M, const fq_packed_ref *w, void *const *outs, int count,
                          fq_stream st);
@@ -44,6 +45,11 @@ int fq_launch_dense_tiled(const void *x, int M, const void *W, int N, int K, voi
 size_t fq_head_nll_scratch_bytes(int M, int V);
 int fq_launch_head_nll(const void *x, int M, const void *W, int V, int K, const int32_t *labels, float *nll,
                        void *workspace, fq_stream st);
+// Attention of one decode step (head dimension 128): rotary embedding of q and k, cache append, softmax over
+// the cached positions.  Workspace of fq_attn_scratch_bytes(Tmax, n_heads) bytes.
+size_t fq_attn_scratch_bytes(int Tmax, int n_heads);
+int fq_launch_attn_decode(const void *q, const void *k, const void *v, void *k_cache, void *v_cache, int pos,
+                          int n_heads, const float *rope, void *out, void *workspace, fq_stream st);
 int fq_launch_glue(int op, const void *a, const void *b, const void *c, int M, int H, void *out, fq_stream st);
 int fq_launch_nll(const void *logits, const int32_t *labels, int M, int V, float *nll, fq_stream st);
 int fq_launch_logit_l2(const void *a, const void *b, int M, int V, float *dist, fq_stream st);

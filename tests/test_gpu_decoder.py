@@ -1,0 +1,185 @@
+"""Real decoder blocks, one decode step (attention over a key/value cache, rotary embedding, residual SwiGLU
+block) through the C-ABI against oracle/decoder_ref.py.  Floating point: outputs within 2e-3 of the row's
+scale like the linears; cache rows of the rotated key within one fp16 ulp (fp32 rotation with an fp32 table
+against fp64), value rows and untouched rows bit-exact."""
+import numpy as np
+import pytest
+
+import fq_synth
+import oracle
+from oracle import decoder_ref as ref
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def torch():
+    import torch
+
+    return torch
+
+
+@pytest.fixture(scope="module")
+def fq():
+    import paper_2501_07139_amd as fq
+
+    return fq
+
+
+def dev(torch, a):
+    return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).cuda().view(torch.float16)
+
+
+def host16(t):
+    return t.cpu().view(__import__("torch").int16).numpy().view(np.float16)
+
+
+def ulps(a, b):
+    """Distance in fp16 steps between two fp16 arrays (same sign assumed where it matters)."""
+    ia = a.view(np.int16).astype(np.int32)
+    ib = b.view(np.int16).astype(np.int32)
+    ia = np.where(ia < 0, -(ia & 0x7FFF), ia)
+    ib = np.where(ib < 0, -(ib & 0x7FFF), ib)
+    return np.abs(ia - ib)
+
+
+def rel_err(y, r):
+    y, r = y.astype(np.float64), r.astype(np.float64)
+    return float(np.max(np.abs(y - r)) / max(np.sqrt(np.mean(r * r)), 1e-30))
+
+
+@pytest.mark.parametrize("case", [(4, 300, (0, 1, 15, 16, 127, 128, 129, 255, 256, 299)), (32, 2048, (2047,)),
+                                  (40, 4096, (4095, 1000))], ids=str)
+def test_attn_decode_against_oracle(fq, torch, case):
+    n_heads, Tmax, positions = case
+    H = 128 * n_heads
+    rng = np.random.default_rng(5)
+    K = (rng.normal(size=(Tmax, H)) * 0.8).astype(np.float16)
+    V = rng.normal(size=(Tmax, H)).astype(np.float16)
+    rope = fq.rope_table(Tmax)
+    for pos in positions:
+        q = (rng.normal(size=H) * 1.5).astype(np.float16)
+        k = rng.normal(size=H).astype(np.float16)
+        v = rng.normal(size=H).astype(np.float16)
+        dK, dV = dev(torch, K), dev(torch, V)
+        got = host16(fq.fq_attn_decode(dev(torch, q), dev(torch, k), dev(torch, v), dK, dV, pos, rope))
+        qr = oracle.round_f16(ref.rope(q, pos, n_heads))
+        kr = oracle.round_f16(ref.rope(k, pos, n_heads))
+        Kw, Vw = K.copy(), V.copy()
+        Kw[pos], Vw[pos] = kr, v
+        want = ref.attention(qr, Kw[:pos + 1], Vw[:pos + 1], n_heads)
+        assert rel_err(got, want) <= 2e-3, pos
+        gK, gV = host16(dK), host16(dV)
+        assert np.array_equal(gV.view(np.uint16), Vw.view(np.uint16)), pos            # value row stored as is
+        keep = np.arange(Tmax) != pos
+        assert np.array_equal(gK[keep].view(np.uint16), K[keep].view(np.uint16)), pos  # other rows untouched
+        d = ulps(gK[pos], kr)
+        assert d.max() <= 1 and np.mean(d == 0) > 0.98, pos
+
+
+def test_attn_decode_closed_forms(fq, torch):
+    n_heads, Tmax = 2, 260
+    H = 256
+    rope = fq.rope_table(Tmax)
+    rng = np.random.default_rng(6)
+    V = rng.normal(size=(Tmax, H)).astype(np.float16)
+    q = rng.normal(size=H).astype(np.float16)
+    zero = np.zeros(H, np.float16)
+    # all keys zero: uniform weights -> the mean of the values, over one split and over three
+    for pos in (0, 99, 259):
+        Kc, Vc = dev(torch, np.zeros((Tmax, H), np.float16)), dev(torch, V)
+        got = host16(fq.fq_attn_decode(dev(torch, q), dev(torch, zero), dev(torch, V[pos]), Kc, Vc, pos, rope))
+        want = V[:pos + 1].astype(np.float64).mean(0)
+        assert np.max(np.abs(got.astype(np.float64) - want)) <= 1e-3 * max(1.0, np.abs(want).max()) + 5e-4, pos
+    # position 0 leaves q and k unrotated: the stored key row is k itself
+    k = rng.normal(size=H).astype(np.float16)
+    Kc, Vc = dev(torch, np.zeros((Tmax, H), np.float16)), dev(torch, np.zeros((Tmax, H), np.float16))
+    out = host16(fq.fq_attn_decode(dev(torch, q), dev(torch, k), dev(torch, V[7]), Kc, Vc, 0, rope))
+    assert np.array_equal(host16(Kc)[0].view(np.uint16), k.view(np.uint16))
+    assert np.array_equal(out.view(np.uint16), V[7].view(np.uint16))                   # one position: its value
+
+
+def build_real_stack(fq, seed, levels=(2, 3, 4, 8)):
+    sh = fq_synth.MODEL_SHAPES["tiny"]
+    layers, host = [], []
+    for l in range(sh["layers"]):
+        mats, hm = [], []
+        for j, (N, K) in enumerate(fq_synth.block_matrix_shapes(sh["hidden"], sh["ffn"])):
+            W = fq_synth.weights(seed, N, K, 0.06, l, j)
+            by, hby = {}, {}
+            for b in levels:
+                codes, s, z = oracle.quantize_rtn(W, b)
+                by[b] = fq.PackedMatrix.from_host(codes, s, z, b)
+                hby[b] = oracle.dequant(codes, s, z)
+            mats.append(by)
+            hm.append(hby)
+        layers.append(mats)
+        host.append(hm)
+    return fq.Stack(layers), host, sh
+
+
+def test_decode_step_against_oracle(fq, torch):
+    stack, host, sh = build_real_stack(fq, 800)
+    L, H, nh, Tmax, T = sh["layers"], sh["hidden"], sh["hidden"] // 128, 140, 134
+    bitvec = fq_synth.bit_vector(801, 7 * L, probs=(0.25, 0.25, 0.25, 0.25))
+    mats = [[host[l][j][int(bitvec[7 * l + j])] for j in range(7)] for l in range(L)]
+    rope = fq.rope_table(Tmax)
+    kc = torch.zeros((L, Tmax, H), dtype=torch.float16, device="cuda")
+    vc = torch.zeros_like(kc)
+    okc, ovc = np.zeros((L, Tmax, H), np.float16), np.zeros((L, Tmax, H), np.float16)
+    X = fq_synth.activations(802, T, H)
+    worst, mean = 0.0, 0.0
+    for pos in range(T):
+        got = host16(fq.fq_decode_step(stack, bitvec, dev(torch, X[pos]), kc, vc, pos, rope))
+        if pos in (0, 1, 2, 17, 127, 128, 133):  # the oracle follows on a sample of positions, from the GPU's caches
+            okc[:], ovc[:] = host16(kc), host16(vc)
+            want = ref.decode_step(X[pos:pos + 1], mats, okc, ovc, pos, nh)[0]
+            diff = np.abs(got.astype(np.float64) - want.astype(np.float64))
+            scale = np.sqrt(np.mean(want.astype(np.float64) ** 2))
+            worst, mean = max(worst, diff.max() / scale), max(mean, diff.mean() / scale)
+            # the rows this step appended, against the oracle's
+            assert np.max(np.abs(host16(kc)[:, pos].astype(np.float64) - okc[:, pos].astype(np.float64))) <= 2e-2
+            assert np.max(np.abs(host16(vc)[:, pos].astype(np.float64) - ovc[:, pos].astype(np.float64))) <= 2e-2
+    # end to end over three blocks: fp16 re-rounding between steps lets single ulps flip
+    assert worst <= 2e-2 and mean <= 2e-3, (worst, mean)
+
+
+def test_decode_block_teacher_forced(fq, torch):
+    """One block at a time from identical inputs and caches: every stored tensor of the block is a few fp16
+    ulps from the oracle's at most."""
+    stack, host, sh = build_real_stack(fq, 810, levels=(3, 4))
+    H, nh, Tmax = sh["hidden"], sh["hidden"] // 128, 150
+    rng = np.random.default_rng(3)
+    rope = fq.rope_table(Tmax)
+    for l, pos, bits in ((0, 0, 4), (1, 64, 3), (2, 149, 4)):
+        sub = fq.Stack([stack.layers[l]])
+        bv = np.full(7, bits, dtype=np.uint8)
+        K0 = (rng.normal(size=(1, Tmax, H)) * 0.7).astype(np.float16)
+        V0 = rng.normal(size=(1, Tmax, H)).astype(np.float16)
+        x = fq_synth.activations(811 + l, 1, H)
+        kc, vc = dev(torch, K0), dev(torch, V0)
+        got = host16(fq.fq_decode_step(sub, bv, dev(torch, x[0]), kc, vc, pos, rope))
+        t = ref.decode_block(x, [host[l][j][bits] for j in range(7)], K0[0], V0[0], pos, nh)
+        want = t["x_next"][0].astype(np.float64)
+        assert np.max(np.abs(got.astype(np.float64) - want)) <= 1e-2 * max(1.0, np.abs(want).max()), (l, pos)
+        assert np.mean(np.abs(got.astype(np.float64) - want)) <= 1e-3
+
+
+def test_decode_step_refuses_bad_arguments(fq, torch):
+    stack, host, sh = build_real_stack(fq, 820, levels=(4,))
+    L, H = sh["layers"], sh["hidden"]
+    bv = np.full(7 * L, 4, dtype=np.uint8)
+    rope = fq.rope_table(16)
+    kc = torch.zeros((L, 16, H), dtype=torch.float16, device="cuda")
+    x = torch.zeros(H, dtype=torch.float16, device="cuda")
+    with pytest.raises(fq.FqError):
+        fq.fq_decode_step(stack, bv, x, kc, kc.clone(), 16, rope)        # pos == Tmax
+    with pytest.raises(fq.FqError):
+        fq.fq_decode_step(stack, bv, x, kc, kc.clone(), -1, rope)
+    with pytest.raises(fq.FqError):
+        fq.fq_decode_step(stack, bv, x, kc, kc.clone(), 0, rope, workspace=torch.empty(64, dtype=torch.uint8, device="cuda"))
+    bad = bv.copy()
+    bad[3] = 8                                                           # not stored
+    with pytest.raises(fq.FqError):
+        fq.fq_decode_step(stack, bad, x, kc, kc.clone(), 0, rope)
+    torch.cuda.synchronize()

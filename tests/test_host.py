@@ -116,6 +116,13 @@ def test_error_codes_without_launching_anything():
     assert lib.fq_head_nll(16, 4, 24, 70, 128, 16, 16, 16, 1 << 20, None) == -5
     assert fq.fq_head_nll_workspace_bytes(4, 70) == 4 * 2 * 8 + 4 * 4 and fq.fq_head_nll_workspace_bytes(0, 70) == 0
     assert fq.fq_head_nll_workspace_bytes(3, 64) % 16 == 0
+    assert lib.fq_attn_decode(None, 16, 16, 16, 16, 0, 8, 2, 16, 16, 16, 1 << 20, None) == -1
+    assert lib.fq_attn_decode(16, 16, 16, 16, 16, 8, 8, 2, 16, 16, 16, 1 << 20, None) == -2     # pos == Tmax
+    assert lib.fq_attn_decode(16, 16, 16, 16, 16, 0, 8, 2, 16, 16, 16, 8, None) == -6
+    assert lib.fq_attn_decode(16, 16, 24, 16, 16, 0, 8, 2, 16, 16, 16, 1 << 20, None) == -5
+    assert fq.fq_attn_workspace_bytes(128, 2) >= 2 * 1 * 130 * 4 and fq.fq_attn_workspace_bytes(129, 2) >= 2 * 2 * 130 * 4
+    assert fq.fq_decode_workspace_bytes(256, 640, 128) >= 8 * 512 + 2 * 1280 + fq.fq_attn_workspace_bytes(128, 2)
+    assert fq.fq_decode_workspace_bytes(200, 640, 128) == 0
     assert lib.fq_glue(9, 16, 16, 16, 1, 128, 16, None) == -2
     assert lib.fq_dense_f16(16, 1, 16, 1, 100, 16, None) == -2
     # the matrix-core kernels address their arrays through 32-bit offsets: 4 GiB of activations is refused

@@ -47,5 +47,5 @@ def test_wait_after_input_copies_counts_the_ring_loads(tmp_path):
         assert "global_load_lds" in lines[j], (kernel, i + 1)
         assert count == n, "%s line %d: vmcnt(%d) but %d loads issued behind the copies" % (kernel, i + 1, n, count)
         found += 1
-    # six input modes x two row counts x (2-bit whole and split, 3-bit whole and split, 4-bit, 8-bit)
-    assert found == 6 * 2 * 6
+    # seven input modes x two row counts x (2-bit whole and split, 3-bit whole and split, 4-bit, 8-bit)
+    assert found == 7 * 2 * 6
