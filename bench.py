@@ -208,29 +208,6 @@ def main():
     l2 = torch.empty(M_FWD, dtype=torch.float32, device=dev)
     ms_l2 = timed(lambda: fq.fq_logit_l2(logits, logits_b, out=l2), reps)
 
-    # beyond the step: a run-time transition, one matrix swapped for its other stored width and back.  The new
-    # packing comes from pinned host memory, so this is a PCIe figure.
-    from paper_2501_07139_amd import elastic
-
-    store = elastic.HostStore([[{int(bitvec[j]): host_q[j], **({swap_bits: swap_q} if j == SWAP_ENTRY else {})}
-                                for j in range(7)]])
-    members = [tuple(int(b) for b in bitvec), tuple(swap_bits if j == SWAP_ENTRY else int(b) for j, b in enumerate(bitvec))]
-    members.sort(key=lambda v: -v[SWAP_ENTRY])
-    hosted = elastic.ElasticModel(store, members)
-    for _ in range(2):  # first use: allocations
-        hosted.move_to(1)
-        hosted.move_to(0)
-    torch.cuda.synchronize()
-    loaded0, t0 = hosted.bytes_loaded, time.perf_counter()
-    for _ in range(5):
-        hosted.move_to(1)
-        hosted.move_to(0)
-    torch.cuda.synchronize()
-    swap_s = (time.perf_counter() - t0) / 10
-    swap_bytes = (hosted.bytes_loaded - loaded0) / 10
-    ms_dec_hosted = timed(lambda: hosted.forward(x_dec), reps)
-    del hosted, store
-
     # the dominant kernel: dequant-GEMM launches of leg A, one by one
     kernels = []
     u = fq.fq_glue(0, x_fwd)
@@ -270,6 +247,56 @@ def main():
         gemv_kernels.append({"matrix": fq_synth.MATRIX_NAMES[j], "N": N, "K": K, "bits": int(bitvec[j]),
                              "us": round(ms * 1e3, 2), "GBps": round(nbytes / ms / 1e6, 1)})
 
+    # beyond the step: the same 8 block copies as real decoder blocks (attention over a key/value cache of
+    # 2048 positions), one token at the last position
+    T_CTX = 2048
+    rope = fq.rope_table(T_CTX)
+    kc = torch.empty((DECODE_LAYERS, HIDDEN // 128, T_CTX, 128), dtype=torch.float16, device=dev).normal_()
+    vc = torch.empty_like(kc).normal_()
+    ws_real = torch.empty(fq.fq_decode_workspace_bytes(HIDDEN, FFN, T_CTX), dtype=torch.uint8, device=dev)
+    x_tok = x_dec.view(-1)
+    y_tok = torch.empty_like(x_tok)
+    ms_real = timed(lambda: fq.fq_decode_step(stack_dec, bitvec_dec, x_tok, kc, vc, T_CTX - 1, rope, out=y_tok,
+                                              workspace=ws_real), reps)
+    q1 = torch.empty(HIDDEN, dtype=torch.float16, device=dev).normal_()
+    a1 = torch.empty_like(q1)
+
+    def attn_rot():  # one call per layer's cache: cold reads
+        for l in range(DECODE_LAYERS):
+            fq.fq_attn_decode(q1, q1, q1, kc[l], vc[l], T_CTX - 1, rope, out=a1, workspace=ws_real)
+
+    attn_rot()
+    torch.cuda.synchronize()
+    attn_graph = torch.cuda.CUDAGraph()  # replayed from a graph: issued from Python the calls are host-bound
+    with torch.cuda.graph(attn_graph):
+        attn_rot()
+    ms_attn = timed(attn_graph.replay, reps) / DECODE_LAYERS
+    kv_bytes = 2.0 * T_CTX * HIDDEN * 2
+    del kc, vc
+
+    # beyond the step: a run-time transition, one matrix swapped for its other stored width and back.  The new
+    # packing comes from pinned host memory, so this is a PCIe figure.
+    from paper_2501_07139_amd import elastic
+
+    store = elastic.HostStore([[{int(bitvec[j]): host_q[j], **({swap_bits: swap_q} if j == SWAP_ENTRY else {})}
+                                for j in range(7)]])
+    members = [tuple(int(b) for b in bitvec), tuple(swap_bits if j == SWAP_ENTRY else int(b) for j, b in enumerate(bitvec))]
+    members.sort(key=lambda v: -v[SWAP_ENTRY])
+    hosted = elastic.ElasticModel(store, members)
+    for _ in range(2):  # first use: allocations
+        hosted.move_to(1)
+        hosted.move_to(0)
+    torch.cuda.synchronize()
+    loaded0, t0 = hosted.bytes_loaded, time.perf_counter()
+    for _ in range(5):
+        hosted.move_to(1)
+        hosted.move_to(0)
+    torch.cuda.synchronize()
+    swap_s = (time.perf_counter() - t0) / 10
+    swap_bytes = (hosted.bytes_loaded - loaded0) / 10
+    ms_dec_hosted = timed(lambda: hosted.forward(x_dec), reps)
+    del hosted, store
+
     traffic = None
     if GEMM_TRAFFIC["kernel_digest"] == kernel_digest() and GEMM_TRAFFIC["fetch_bytes"]:
         traffic = {"fetch_bytes": GEMM_TRAFFIC["fetch_bytes"], "write_bytes": GEMM_TRAFFIC["write_bytes"]}
@@ -302,6 +329,12 @@ def main():
                                            "max_abs_diff_to_fused": float((nll_two - nll).abs().max().item())},
             "logit_l2_outside_the_step": {"GBps": round(2 * nll_bytes / ms_l2 / 1e6, 1), "ms": round(ms_l2, 4),
                                           "frac_hbm_peak": round(2 * nll_bytes / ms_l2 / 1e6 / PEAK_HBM_GBPS, 4)},
+            "real_decode_outside_the_step": {"context": T_CTX, "layers": DECODE_LAYERS, "ms": round(ms_real, 4),
+                                             "us_per_block": round(ms_real * 1e3 / DECODE_LAYERS, 2),
+                                             "GBps_weights_and_cache": round((gemv_bytes + DECODE_LAYERS * kv_bytes) / ms_real / 1e6, 1),
+                                             "attention_us": round(ms_attn * 1e3, 2),
+                                             "attention_GBps": round(kv_bytes / ms_attn / 1e6, 1),
+                                             "attention_frac_hbm_peak": round(kv_bytes / ms_attn / 1e6 / PEAK_HBM_GBPS, 4)},
             "transition_outside_the_step": {"matrix": fq_synth.MATRIX_NAMES[SWAP_ENTRY], "widths": [int(bitvec[SWAP_ENTRY]), swap_bits],
                                             "ms_per_swap": round(swap_s * 1e3, 3), "MB_loaded_per_swap": round(swap_bytes / 1e6, 2),
                                             "GBps_host_to_device": round(swap_bytes / swap_s / 1e9, 1),

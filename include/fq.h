@@ -234,15 +234,16 @@ int fq_logit_l2(const void *a, const void *b, int M, int V, float *dist_out, voi
  * is stored as fp16.
  *
  * fq_attn_decode: the attention step alone.  q, k, v fp16 [H] (H = 128 n_heads),
- * device, read.  k_cache, v_cache fp16 [Tmax,H], device: rows < pos read, row pos
+ * device, read.  k_cache, v_cache fp16 [n_heads][Tmax][128] (head-major: a
+ * head's positions are contiguous), device: positions < pos read, position pos
  * written.  rope fp32 [Tmax][64][2] = (cos, sin) of pos * theta_i, device, read.
  * out fp16 [H], device, written.  workspace: device scratch of at least
  * fq_attn_workspace_bytes(Tmax, n_heads) bytes, 16-byte aligned, owned by the
- * caller.  FQ_ERR_SHAPE unless 0 <= pos < Tmax.
+ * caller.  FQ_ERR_SHAPE unless 0 <= pos < Tmax <= 131072.
  *
  * fq_decode_step: L blocks.  layers/bitvec as in fq_stack_forward.  x_in, x_out
- * fp16 [hidden], device.  k_cache, v_cache fp16 [L,Tmax,hidden], device, layer l
- * at offset l*Tmax*hidden.  workspace of fq_decode_workspace_bytes(hidden, ffn,
+ * fp16 [hidden], device.  k_cache, v_cache fp16 [L][n_heads][Tmax][128], device,
+ * layer l at offset l*Tmax*hidden.  workspace of fq_decode_workspace_bytes(hidden, ffn,
  * Tmax) bytes, 16-byte aligned.  Six launches per block (q/k/v, attention and
  * its merge when pos >= 128, o, gate/up, down), all on `stream`; positions must
  * be fed in order 0, 1, 2, ... for the cache to be complete.

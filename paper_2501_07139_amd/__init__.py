@@ -351,9 +351,12 @@ def fq_attn_decode(q, k, v, k_cache, v_cache, pos: int, rope, out=None, workspac
     q, k, v = (_dev(t, torch.float16, n) for t, n in ((q, "q"), (k, "k"), (v, "v")))
     k_cache, v_cache = _dev(k_cache, torch.float16, "k_cache"), _dev(v_cache, torch.float16, "v_cache")
     rope = _dev(rope, torch.float32, "rope")
-    Tmax, H = k_cache.shape
-    if q.numel() != H or k.numel() != H or v.numel() != H or v_cache.shape != k_cache.shape or H % 128:
-        raise ValueError("fq_attn_decode: q, k, v [H], caches [Tmax,H], H a multiple of 128")
+    if k_cache.dim() != 3 or k_cache.shape[2] != 128 or v_cache.shape != k_cache.shape:
+        raise ValueError("fq_attn_decode: caches [n_heads, Tmax, 128]")
+    n_heads, Tmax, _ = k_cache.shape
+    H = 128 * n_heads
+    if q.numel() != H or k.numel() != H or v.numel() != H:
+        raise ValueError("fq_attn_decode: q, k, v [128 n_heads]")
     if rope.shape[0] < Tmax or tuple(rope.shape[1:]) != (64, 2):
         raise ValueError("fq_attn_decode: rope must be [>=Tmax, 64, 2]")
     if out is None:
@@ -366,7 +369,7 @@ def fq_attn_decode(q, k, v, k_cache, v_cache, pos: int, rope, out=None, workspac
 
 
 def fq_decode_step(stack: Stack, bitvec, x, k_cache, v_cache, pos: int, rope, out=None, workspace=None, stream=None):
-    """One token through the stack's blocks as real decoder blocks; caches fp16 [L,Tmax,hidden]."""
+    """One token through the stack's blocks as real decoder blocks; caches fp16 [L, n_heads, Tmax, 128]."""
     torch = _torch()
     x = _dev(x, torch.float16, "x")
     k_cache, v_cache = _dev(k_cache, torch.float16, "k_cache"), _dev(v_cache, torch.float16, "v_cache")
@@ -374,9 +377,12 @@ def fq_decode_step(stack: Stack, bitvec, x, k_cache, v_cache, pos: int, rope, ou
     bitvec = np.ascontiguousarray(bitvec, dtype=np.uint8)
     if bitvec.size != 7 * stack.L:
         raise ValueError("bitvec needs 7 entries per block")
-    L, Tmax, H = k_cache.shape
-    if L != stack.L or H != stack.hidden or v_cache.shape != k_cache.shape or x.numel() != H:
-        raise ValueError("fq_decode_step: x [hidden], caches [L,Tmax,hidden]")
+    if k_cache.dim() != 4 or k_cache.shape[3] != 128 or v_cache.shape != k_cache.shape:
+        raise ValueError("fq_decode_step: caches [L, n_heads, Tmax, 128]")
+    L, n_heads, Tmax, _ = k_cache.shape
+    H = 128 * n_heads
+    if L != stack.L or H != stack.hidden or x.numel() != H:
+        raise ValueError("fq_decode_step: x [hidden], caches [L, hidden/128, Tmax, 128]")
     if rope.shape[0] < Tmax or tuple(rope.shape[1:]) != (64, 2):
         raise ValueError("fq_decode_step: rope must be [>=Tmax, 64, 2]")
     if out is None:

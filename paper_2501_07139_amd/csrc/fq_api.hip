@@ -294,15 +294,16 @@ extern "C" int fq_attn_decode(const void *q, const void *k, const void *v, void 
 {
     if (!q || !k || !v || !k_cache || !v_cache || !rope || !out || !workspace)
         return fq_fail(FQ_ERR_NULL, "fq_attn_decode: NULL argument");
-    if (n_heads <= 0 || Tmax <= 0 || pos < 0 || pos >= Tmax)
-        return fq_fail(FQ_ERR_SHAPE, "fq_attn_decode: n_heads=%d Tmax=%d pos=%d (need 0 <= pos < Tmax)", n_heads, Tmax, pos);
+    if (n_heads <= 0 || Tmax <= 0 || Tmax > fq_attn_max_positions() || pos < 0 || pos >= Tmax)
+        return fq_fail(FQ_ERR_SHAPE, "fq_attn_decode: n_heads=%d Tmax=%d pos=%d (need 0 <= pos < Tmax <= %d)", n_heads, Tmax,
+                       pos, fq_attn_max_positions());
     if (workspace_bytes < fq_attn_scratch_bytes(Tmax, n_heads))
         return fq_fail(FQ_ERR_WORKSPACE, "fq_attn_decode: workspace of %zu bytes, need %zu", workspace_bytes,
                        fq_attn_scratch_bytes(Tmax, n_heads));
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(k_cache) || !aligned16(v_cache) ||
         !aligned16(rope) || !aligned16(out) || !aligned16(workspace))
         return fq_fail(FQ_ERR_ALIGN, "fq_attn_decode: pointers must be 16-byte aligned");
-    return check_hip(fq_launch_attn_decode(q, k, v, k_cache, v_cache, pos, n_heads, rope, out, workspace,
+    return check_hip(fq_launch_attn_decode(q, k, v, k_cache, v_cache, pos, Tmax, n_heads, rope, out, workspace,
                                            static_cast<fq_stream>(stream)), "fq_attn_decode launch");
 }
 
@@ -312,8 +313,9 @@ extern "C" int fq_decode_step(const fq_layer *layers, int L, const uint8_t *bitv
 {
     if (!layers || !bitvec || !x_in || !x_out || !k_cache || !v_cache || !rope || !workspace)
         return fq_fail(FQ_ERR_NULL, "fq_decode_step: NULL argument");
-    if (L <= 0 || Tmax <= 0 || pos < 0 || pos >= Tmax)
-        return fq_fail(FQ_ERR_SHAPE, "fq_decode_step: L=%d Tmax=%d pos=%d (need 0 <= pos < Tmax)", L, Tmax, pos);
+    if (L <= 0 || Tmax <= 0 || Tmax > fq_attn_max_positions() || pos < 0 || pos >= Tmax)
+        return fq_fail(FQ_ERR_SHAPE, "fq_decode_step: L=%d Tmax=%d pos=%d (need 0 <= pos < Tmax <= %d)", L, Tmax, pos,
+                       fq_attn_max_positions());
     int H = 0, F = 0;
     if (int rc = validate_layers("fq_decode_step", layers, L, bitvec, &H, &F))
         return rc;
@@ -356,7 +358,7 @@ extern "C" int fq_decode_step(const fq_layer *layers, int L, const uint8_t *bitv
             xres = xc;
         FQ_STEP(check_hip(fq_launch_gemv_multi(in_qkv, 1, &sel[0], qkv, 3, st), "decode q/k/v"));
         FQ_STEP(check_hip(fq_launch_attn_decode(q, k, v, static_cast<char *>(k_cache) + l * layer_cache,
-                                                static_cast<char *>(v_cache) + l * layer_cache, pos, n_heads, rope, a,
+                                                static_cast<char *>(v_cache) + l * layer_cache, pos, Tmax, n_heads, rope, a,
                                                 attn, st), "decode attention"));
         FQ_STEP(check_hip(fq_launch_gemv_multi(fq_gemv_input{a, nullptr, nullptr, nullptr, 0}, 1, &sel[3], &o, 1, st),
                           "decode o"));

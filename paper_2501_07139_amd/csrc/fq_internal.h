@@ -46,10 +46,11 @@ size_t fq_head_nll_scratch_bytes(int M, int V);
 int fq_launch_head_nll(const void *x, int M, const void *W, int V, int K, const int32_t *labels, float *nll,
                        void *workspace, fq_stream st);
 // Attention of one decode step (head dimension 128): rotary embedding of q and k, cache append, softmax over
-// the cached positions.  Workspace of fq_attn_scratch_bytes(Tmax, n_heads) bytes.
+// the cached positions; caches [heads][Tmax][128].  Workspace of fq_attn_scratch_bytes(Tmax, n_heads) bytes.
 size_t fq_attn_scratch_bytes(int Tmax, int n_heads);
+int fq_attn_max_positions(); // largest Tmax the merge of the splits handles
 int fq_launch_attn_decode(const void *q, const void *k, const void *v, void *k_cache, void *v_cache, int pos,
-                          int n_heads, const float *rope, void *out, void *workspace, fq_stream st);
+                          int Tmax, int n_heads, const float *rope, void *out, void *workspace, fq_stream st);
 int fq_launch_glue(int op, const void *a, const void *b, const void *c, int M, int H, void *out, fq_stream st);
 int fq_launch_nll(const void *logits, const int32_t *labels, int M, int V, float *nll, fq_stream st);
 int fq_launch_logit_l2(const void *a, const void *b, int M, int V, float *dist, fq_stream st);

@@ -34,6 +34,17 @@ def host16(t):
     return t.cpu().view(__import__("torch").int16).numpy().view(np.float16)
 
 
+def to_heads(a, n_heads):
+    """[..., T, H] position-major (the reference's) -> [..., n_heads, T, 128] head-major (the library's)."""
+    a = np.asarray(a)
+    return np.ascontiguousarray(np.swapaxes(a.reshape(a.shape[:-1] + (n_heads, 128)), -3, -2))
+
+
+def from_heads(a):
+    a = np.swapaxes(np.asarray(a), -3, -2)
+    return np.ascontiguousarray(a).reshape(a.shape[:-2] + (-1,))
+
+
 def ulps(a, b):
     """Distance in fp16 steps between two fp16 arrays (same sign assumed where it matters)."""
     ia = a.view(np.int16).astype(np.int32)
@@ -61,7 +72,7 @@ def test_attn_decode_against_oracle(fq, torch, case):
         q = (rng.normal(size=H) * 1.5).astype(np.float16)
         k = rng.normal(size=H).astype(np.float16)
         v = rng.normal(size=H).astype(np.float16)
-        dK, dV = dev(torch, K), dev(torch, V)
+        dK, dV = dev(torch, to_heads(K, n_heads)), dev(torch, to_heads(V, n_heads))
         got = host16(fq.fq_attn_decode(dev(torch, q), dev(torch, k), dev(torch, v), dK, dV, pos, rope))
         qr = oracle.round_f16(ref.rope(q, pos, n_heads))
         kr = oracle.round_f16(ref.rope(k, pos, n_heads))
@@ -69,7 +80,7 @@ def test_attn_decode_against_oracle(fq, torch, case):
         Kw[pos], Vw[pos] = kr, v
         want = ref.attention(qr, Kw[:pos + 1], Vw[:pos + 1], n_heads)
         assert rel_err(got, want) <= 2e-3, pos
-        gK, gV = host16(dK), host16(dV)
+        gK, gV = from_heads(host16(dK)), from_heads(host16(dV))
         assert np.array_equal(gV.view(np.uint16), Vw.view(np.uint16)), pos            # value row stored as is
         keep = np.arange(Tmax) != pos
         assert np.array_equal(gK[keep].view(np.uint16), K[keep].view(np.uint16)), pos  # other rows untouched
@@ -87,15 +98,15 @@ def test_attn_decode_closed_forms(fq, torch):
     zero = np.zeros(H, np.float16)
     # all keys zero: uniform weights -> the mean of the values, over one split and over three
     for pos in (0, 99, 259):
-        Kc, Vc = dev(torch, np.zeros((Tmax, H), np.float16)), dev(torch, V)
+        Kc, Vc = dev(torch, np.zeros((n_heads, Tmax, 128), np.float16)), dev(torch, to_heads(V, n_heads))
         got = host16(fq.fq_attn_decode(dev(torch, q), dev(torch, zero), dev(torch, V[pos]), Kc, Vc, pos, rope))
         want = V[:pos + 1].astype(np.float64).mean(0)
         assert np.max(np.abs(got.astype(np.float64) - want)) <= 1e-3 * max(1.0, np.abs(want).max()) + 5e-4, pos
     # position 0 leaves q and k unrotated: the stored key row is k itself
     k = rng.normal(size=H).astype(np.float16)
-    Kc, Vc = dev(torch, np.zeros((Tmax, H), np.float16)), dev(torch, np.zeros((Tmax, H), np.float16))
+    Kc, Vc = (dev(torch, np.zeros((n_heads, Tmax, 128), np.float16)) for _ in range(2))
     out = host16(fq.fq_attn_decode(dev(torch, q), dev(torch, k), dev(torch, V[7]), Kc, Vc, 0, rope))
-    assert np.array_equal(host16(Kc)[0].view(np.uint16), k.view(np.uint16))
+    assert np.array_equal(from_heads(host16(Kc))[0].view(np.uint16), k.view(np.uint16))
     assert np.array_equal(out.view(np.uint16), V[7].view(np.uint16))                   # one position: its value
 
 
@@ -124,7 +135,7 @@ def test_decode_step_against_oracle(fq, torch):
     bitvec = fq_synth.bit_vector(801, 7 * L, probs=(0.25, 0.25, 0.25, 0.25))
     mats = [[host[l][j][int(bitvec[7 * l + j])] for j in range(7)] for l in range(L)]
     rope = fq.rope_table(Tmax)
-    kc = torch.zeros((L, Tmax, H), dtype=torch.float16, device="cuda")
+    kc = torch.zeros((L, nh, Tmax, 128), dtype=torch.float16, device="cuda")
     vc = torch.zeros_like(kc)
     okc, ovc = np.zeros((L, Tmax, H), np.float16), np.zeros((L, Tmax, H), np.float16)
     X = fq_synth.activations(802, T, H)
@@ -132,14 +143,14 @@ def test_decode_step_against_oracle(fq, torch):
     for pos in range(T):
         got = host16(fq.fq_decode_step(stack, bitvec, dev(torch, X[pos]), kc, vc, pos, rope))
         if pos in (0, 1, 2, 17, 127, 128, 133):  # the oracle follows on a sample of positions, from the GPU's caches
-            okc[:], ovc[:] = host16(kc), host16(vc)
+            okc[:], ovc[:] = from_heads(host16(kc)), from_heads(host16(vc))
             want = ref.decode_step(X[pos:pos + 1], mats, okc, ovc, pos, nh)[0]
             diff = np.abs(got.astype(np.float64) - want.astype(np.float64))
             scale = np.sqrt(np.mean(want.astype(np.float64) ** 2))
             worst, mean = max(worst, diff.max() / scale), max(mean, diff.mean() / scale)
             # the rows this step appended, against the oracle's
-            assert np.max(np.abs(host16(kc)[:, pos].astype(np.float64) - okc[:, pos].astype(np.float64))) <= 2e-2
-            assert np.max(np.abs(host16(vc)[:, pos].astype(np.float64) - ovc[:, pos].astype(np.float64))) <= 2e-2
+            assert np.max(np.abs(from_heads(host16(kc))[:, pos].astype(np.float64) - okc[:, pos].astype(np.float64))) <= 2e-2
+            assert np.max(np.abs(from_heads(host16(vc))[:, pos].astype(np.float64) - ovc[:, pos].astype(np.float64))) <= 2e-2
     # end to end over three blocks: fp16 re-rounding between steps lets single ulps flip
     assert worst <= 2e-2 and mean <= 2e-3, (worst, mean)
 
@@ -157,7 +168,7 @@ def test_decode_block_teacher_forced(fq, torch):
         K0 = (rng.normal(size=(1, Tmax, H)) * 0.7).astype(np.float16)
         V0 = rng.normal(size=(1, Tmax, H)).astype(np.float16)
         x = fq_synth.activations(811 + l, 1, H)
-        kc, vc = dev(torch, K0), dev(torch, V0)
+        kc, vc = dev(torch, to_heads(K0, nh)), dev(torch, to_heads(V0, nh))
         got = host16(fq.fq_decode_step(sub, bv, dev(torch, x[0]), kc, vc, pos, rope))
         t = ref.decode_block(x, [host[l][j][bits] for j in range(7)], K0[0], V0[0], pos, nh)
         want = t["x_next"][0].astype(np.float64)
@@ -170,7 +181,7 @@ def test_decode_step_refuses_bad_arguments(fq, torch):
     L, H = sh["layers"], sh["hidden"]
     bv = np.full(7 * L, 4, dtype=np.uint8)
     rope = fq.rope_table(16)
-    kc = torch.zeros((L, 16, H), dtype=torch.float16, device="cuda")
+    kc = torch.zeros((L, H // 128, 16, 128), dtype=torch.float16, device="cuda")
     x = torch.zeros(H, dtype=torch.float16, device="cuda")
     with pytest.raises(fq.FqError):
         fq.fq_decode_step(stack, bv, x, kc, kc.clone(), 16, rope)        # pos == Tmax
