@@ -46,6 +46,16 @@ int qlinear_checked(const void *x, int M, const fq_packed_ref &w, void *out, fq_
     return check_hip(e, "fq_qlinear launch");
 }
 
+// M > 16: the linears that share an input (q/k/v, gate/up) in one launch.
+int qlinear_multi_checked(const void *x, int M, const fq_packed_ref *w, void *const *outs, int count, fq_stream st)
+{
+    for (int i = 0; i < count; ++i)
+        if (!below_4gib(M, w[i].K, 2) || !below_4gib(((size_t)w[i].N + 63) / 64 * 8, w[i].K, w[i].bits))
+            return fq_fail(FQ_ERR_SHAPE, "fq_stack_forward: M=%d N=%d K=%d: activations and packed weights must each "
+                           "stay below 4 GiB", M, w[i].N, w[i].K);
+    return check_hip(fq_launch_gemm_multi(x, M, w, outs, count, st), "fq_stack_forward linears");
+}
+
 constexpr int kMaxGlueH = 16384;
 
 size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
@@ -256,14 +266,12 @@ extern "C" int fq_stack_forward(const fq_layer *layers, int L, const uint8_t *bi
             continue;
         }
         FQ_STEP(check_hip(fq_launch_glue(0, xcur, nullptr, nullptr, M, H, u, st), "glue rms"));
-        for (int j = 0; j < 3; ++j)
-            FQ_STEP(qlinear_checked(u, M, sel[j], qkv[j], st));
+        FQ_STEP(qlinear_multi_checked(u, M, &sel[0], qkv, 3, st));
         FQ_STEP(check_hip(fq_launch_glue(1, q, k, v, M, H, a, st), "glue rms(q+k+v)"));
         FQ_STEP(qlinear_checked(a, M, sel[3], o, st));
         FQ_STEP(check_hip(fq_launch_glue(2, xcur, o, nullptr, M, H, x1, st), "glue add"));
         FQ_STEP(check_hip(fq_launch_glue(0, x1, nullptr, nullptr, M, H, u2, st), "glue rms"));
-        for (int j = 0; j < 2; ++j)
-            FQ_STEP(qlinear_checked(u2, M, sel[4 + j], gp[j], st));
+        FQ_STEP(qlinear_multi_checked(u2, M, &sel[4], gp, 2, st));
         FQ_STEP(check_hip(fq_launch_glue(3, g, p, nullptr, M, F, mm, st), "glue rms(silu*mul)"));
         FQ_STEP(qlinear_checked(mm, M, sel[6], d, st));
         FQ_STEP(check_hip(fq_launch_glue(4, x1, d, nullptr, M, H, xnext, st), "glue rms(add)"));

@@ -18,6 +18,10 @@
 // both free of bank conflicts; the copy goes from global memory straight into LDS.  Loads for group g+1 are issued
 // before the MFMAs of group g; one barrier per iteration.
 //
+// The linears of a block that share their input (q/k/v, gate/up) go out as one launch whose workgroups
+// each look up their matrix: a matrix whose tiles do not fill the workgroup slots a whole number of times
+// shares its last round with the next one.
+//
 // The unquantized head runs the same kernel: its fp16 weights are read from the row-major matrix
 // directly into the operand registers (sixteen rows by 64 contiguous bytes per load).
 #include "fq_device.h"
@@ -73,29 +77,19 @@ __device__ __forceinline__ void load_wchunk(WChunk<BITS> &w, const GemmBuffers &
     }
 }
 
-// Two workgroups per CU (two wavefronts per SIMD): a single wavefront cannot keep the matrix pipe
-// busy, and two independent workgroups overlap one's unpack/copy phase with the other's MFMAs.
+// One output tile of one matrix.  Xs: the workgroup's two activation tiles in LDS, [2][QBM * 16], chunk ch of
+// row r at r*16 + (ch ^ (r & 15)).  `tile` numbers the matrix's tiles in bands of four activation row-tiles
+// (row-tile fastest): tiles with consecutive numbers share weight tiles and a few activation row-tiles.
 template <int BITS, int QNB>
-__global__ __launch_bounds__(256, 2) void qgemm_kernel(const _Float16 *__restrict__ x, int M,
-                                                       const uint32_t *__restrict__ packed,
-                                                       const _Float16 *__restrict__ scales,
-                                                       const _Float16 *__restrict__ zeros, int N, int K,
-                                                       _Float16 *__restrict__ out)
+__device__ __forceinline__ void qgemm_tile(h8 (*Xs)[QBM * 16], const _Float16 *__restrict__ x, int M,
+                                           const uint32_t *__restrict__ packed, const _Float16 *__restrict__ scales,
+                                           const _Float16 *__restrict__ zeros, int N, int K,
+                                           _Float16 *__restrict__ out, int tile)
 {
-    __shared__ h8 Xs[2][QBM * 16]; // chunk ch of row r at r*16 + (ch ^ (r & 15))
-
     constexpr int QBN = 64 * QNB;
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    // Workgroups are dealt to the eight XCDs round-robin and each XCD has its own L2.  Give XCD x the
-    // x-th contiguous run of tiles, and order tiles in bands of four activation row-tiles (row-tile
-    // fastest): the tiles resident on one XCD then form a block of about 4 x 16, so its L2 fetches a few
-    // activation row-tiles and a few weight tiles instead of a whole matrix.
-    const int NT = (N + QBN - 1) / QBN, MT = (M + QBM - 1) / QBM, total = NT * MT;
-    const int per_xcd = (total + 7) >> 3;
-    const int tile = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-    if (tile >= total)
-        return; // uniform over the workgroup, before any barrier
+    const int NT = (N + QBN - 1) / QBN, MT = (M + QBM - 1) / QBM;
     const int band = tile / (4 * NT), rest = tile - band * 4 * NT, height = min(4, MT - 4 * band);
     const int m0 = (4 * band + rest % height) * QBM, n0 = (rest / height) * QBN;
     const int G = K >> 7;
@@ -235,6 +229,70 @@ __global__ __launch_bounds__(256, 2) void qgemm_kernel(const _Float16 *__restric
     }
 }
 
+// Workgroups are dealt to the eight XCDs round-robin and each XCD has its own L2: XCD x takes the x-th
+// contiguous run of `total` tiles.  Returns -1 for the workgroups past the end (uniform over a workgroup).
+__device__ __forceinline__ int xcd_tile(int total)
+{
+    const int per_xcd = (total + 7) >> 3;
+    const int tile = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    return tile < total ? tile : -1;
+}
+
+// Two workgroups per CU (two wavefronts per SIMD): a single wavefront cannot keep the matrix pipe
+// busy, and two independent workgroups overlap one's unpack/copy phase with the other's MFMAs.
+template <int BITS, int QNB>
+__global__ __launch_bounds__(256, 2) void qgemm_kernel(const _Float16 *__restrict__ x, int M,
+                                                       const uint32_t *__restrict__ packed,
+                                                       const _Float16 *__restrict__ scales,
+                                                       const _Float16 *__restrict__ zeros, int N, int K,
+                                                       _Float16 *__restrict__ out)
+{
+    __shared__ h8 Xs[2][QBM * 16];
+    constexpr int QBN = 64 * QNB;
+    const int tile = xcd_tile(((N + QBN - 1) / QBN) * ((M + QBM - 1) / QBM));
+    if (tile < 0)
+        return; // before any barrier
+    qgemm_tile<BITS, QNB>(Xs, x, M, packed, scales, zeros, N, K, out, tile);
+}
+
+// Up to three matrices with the same input in one launch (q/k/v, gate/up): their tiles form one list, so
+// a matrix whose tiles do not fill the chip's workgroup slots a whole number of times shares its last
+// round with the next matrix.  Each workgroup looks up its matrix and runs the tile code of that matrix's
+// bit-width and tile width.
+struct GemmJob {
+    const uint32_t *packed;
+    const _Float16 *scales, *zeros;
+    _Float16 *out;
+    int N, bits, qnb, tile0; // tile0: index of the matrix's first tile in the launch's list
+};
+struct GemmJobs {
+    GemmJob j[3];
+    int count, total;
+};
+
+__global__ __launch_bounds__(256, 2) void qgemm_multi_kernel(const _Float16 *__restrict__ x, int M, int K, GemmJobs jobs)
+{
+    __shared__ h8 Xs[2][QBM * 16];
+    int tile = xcd_tile(jobs.total);
+    if (tile < 0)
+        return;
+    int ji = 0;
+    if (jobs.count > 1 && tile >= jobs.j[1].tile0)
+        ji = 1;
+    if (jobs.count > 2 && tile >= jobs.j[2].tile0)
+        ji = 2;
+    const GemmJob job = ji == 0 ? jobs.j[0] : (ji == 1 ? jobs.j[1] : jobs.j[2]); // selected by value
+    tile -= job.tile0;
+    switch (job.bits * 8 + job.qnb) {
+    case 2 * 8 + 4: qgemm_tile<2, 4>(Xs, x, M, job.packed, job.scales, job.zeros, job.N, K, job.out, tile); break;
+    case 4 * 8 + 4: qgemm_tile<4, 4>(Xs, x, M, job.packed, job.scales, job.zeros, job.N, K, job.out, tile); break;
+    case 2 * 8 + 2: qgemm_tile<2, 2>(Xs, x, M, job.packed, job.scales, job.zeros, job.N, K, job.out, tile); break;
+    case 3 * 8 + 2: qgemm_tile<3, 2>(Xs, x, M, job.packed, job.scales, job.zeros, job.N, K, job.out, tile); break;
+    case 4 * 8 + 2: qgemm_tile<4, 2>(Xs, x, M, job.packed, job.scales, job.zeros, job.N, K, job.out, tile); break;
+    default: qgemm_tile<8, 2>(Xs, x, M, job.packed, job.scales, job.zeros, job.N, K, job.out, tile); break;
+    }
+}
+
 // Weight-tile width.  Wide tiles (each wavefront 128 x 64) halve the LDS reads and activation copies per
 // MFMA but need at least two workgroups per CU to keep both wavefront slots of every SIMD filled.
 int wide_tiles_pay(int M, int N)
@@ -281,6 +339,30 @@ int fq_launch_gemm(const void *x, int M, const fq_packed_ref &w, void *out, fq_s
     case 4: return launch_q<4>(x, M, w, out, st);
     default: return launch_q<8>(x, M, w, out, st);
     }
+}
+
+// Matrices that share x (same K): one launch.  Shapes are validated by the caller like fq_launch_gemm's.
+int fq_launch_gemm_multi(const void *x, int M, const fq_packed_ref *w, void *const *outs, int count, fq_stream st)
+{
+    if (count < 1 || count > 3)
+        return (int)hipErrorInvalidValue;
+    GemmJobs jobs;
+    jobs.count = count;
+    int total = 0;
+    for (int i = 0; i < count; ++i) {
+        const size_t Np = ((size_t)w[i].N + 63) / 64 * 64;
+        if (w[i].K != w[0].K || !fits_32bit(M, w[i].K, 2) || Np / 8 * w[i].K * w[i].bits >= ((size_t)1 << 32))
+            return (int)hipErrorInvalidValue;
+        const int qnb = ((w[i].bits == 2 || w[i].bits == 4) && wide_tiles_pay(M, w[i].N)) ? 4 : 2;
+        jobs.j[i] = GemmJob{static_cast<const uint32_t *>(w[i].packed), static_cast<const _Float16 *>(w[i].scales),
+                            static_cast<const _Float16 *>(w[i].zeros), static_cast<_Float16 *>(outs[i]), w[i].N,
+                            w[i].bits, qnb, total};
+        total += ((w[i].N + 64 * qnb - 1) / (64 * qnb)) * ((M + QBM - 1) / QBM);
+    }
+    jobs.total = total;
+    hipLaunchKernelGGL(qgemm_multi_kernel, dim3(8 * ((total + 7) / 8)), dim3(256), 0, st,
+                       static_cast<const _Float16 *>(x), M, w[0].K, jobs);
+    return (int)hipGetLastError();
 }
 
 int fq_launch_dense(const void *x, int M, const void *W, int N, int K, void *out, fq_stream st)

@@ -37,6 +37,8 @@ bool fq_gemv_can_stream(int M, int K, int bits, int inputs);
 int fq_launch_gemv_multi(const fq_gemv_input &src, int M, const fq_packed_ref *w, void *const *outs, int count,
                          fq_stream st);
 int fq_launch_gemm(const void *x, int M, const fq_packed_ref &w, void *out, fq_stream st);
+// Up to three matrices with the same input (same K) in one launch, M > 16.
+int fq_launch_gemm_multi(const void *x, int M, const fq_packed_ref *w, void *const *outs, int count, fq_stream st);
 int fq_launch_dense(const void *x, int M, const void *W, int N, int K, void *out, fq_stream st);
 // The same product with 256 x 256 tiles, both operands through LDS; pays once its tiles fill the chip.
 bool fq_dense_tiled_pays(int M, int N);
