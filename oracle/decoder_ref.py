@@ -85,15 +85,13 @@ def decode_step(x, layer_mats, k_caches, v_caches, pos, n_heads):
     return x
 
 
-def sequence_block(X, mats, n_heads):
-    """The same block over a whole sequence at once, X fp16 [T,H] (row t at position t): the attention is the
-    masked T x T product.  Another route to what T calls of decode_block give; used to pin them."""
-    wq, wk, wv, wo, wg, wu, wd = mats
+def sequence_attention(q, k, v, n_heads):
+    """Causal attention over a whole sequence: q, k, v fp16 [T,H], row t at position t.  Returns
+    (a fp16 [T,H], rotated keys fp16 [T,H]); the values enter the cache as they are.  The masked T x T
+    product: another route to what T calls of attention() on a growing cache give."""
     r16 = oracle.round_f16
-    T, H = X.shape
+    T, H = q.shape
     d = H // n_heads
-    u = oracle.rms_rows(_f64(X))
-    q, k, v = (r16(oracle.qlinear(u, w)) for w in (wq, wk, wv))
     qr = r16(np.stack([rope(q[t], t, n_heads) for t in range(T)]))
     kr = r16(np.stack([rope(k[t], t, n_heads) for t in range(T)]))
     a = np.empty((T, H))
@@ -104,7 +102,21 @@ def sequence_block(X, mats, n_heads):
         s[mask] = -np.inf
         w = np.exp(s - s.max(axis=1, keepdims=True))
         a[:, sl] = (w / w.sum(axis=1, keepdims=True)) @ _f64(v[:, sl])
-    a = r16(a)
+    return r16(a), kr
+
+
+def sequence_block(X, mats, n_heads, k_cache=None, v_cache=None):
+    """The block over a whole sequence at once, X fp16 [T,H] (row t at position t); fills rows 0..T-1 of the
+    caches (fp16 [Tmax,H]) when given.  Used to pin token-by-token decoding and as the prefill reference."""
+    wq, wk, wv, wo, wg, wu, wd = mats
+    r16 = oracle.round_f16
+    T = X.shape[0]
+    u = oracle.rms_rows(_f64(X))
+    q, k, v = (r16(oracle.qlinear(u, w)) for w in (wq, wk, wv))
+    a, kr = sequence_attention(q, k, v, n_heads)
+    if k_cache is not None:
+        k_cache[:T] = kr
+        v_cache[:T] = v
     o = r16(oracle.qlinear(a, wo))
     x1 = r16(_f64(X) + _f64(o))
     u2 = oracle.rms_rows(_f64(x1))
@@ -112,3 +124,10 @@ def sequence_block(X, mats, n_heads):
     m = r16(oracle.silu_mul(g, p))
     dd = r16(oracle.qlinear(m, wd))
     return r16(_f64(x1) + _f64(dd))
+
+
+def sequence_stack(X, layer_mats, n_heads, k_caches=None, v_caches=None):
+    for l, mats in enumerate(layer_mats):
+        X = sequence_block(X, mats, n_heads, None if k_caches is None else k_caches[l],
+                           None if v_caches is None else v_caches[l])
+    return X

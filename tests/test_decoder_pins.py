@@ -157,6 +157,28 @@ def test_token_by_token_decoding_equals_the_masked_sequence_product():
     assert all(np.array_equal(rows[t], rows2[t]) for t in range(4)) and not np.array_equal(rows[5], rows2[5])
 
 
+def test_sequence_attention_rows_are_the_decode_attention():
+    rng = np.random.default_rng(4)
+    T, nh = 9, 2
+    H = 128 * nh
+    q, k, v = (rng.normal(size=(T, H)).astype(np.float16) for _ in range(3))
+    a, kr = ref.sequence_attention(q, k, v, nh)
+    for t in range(T):
+        assert np.array_equal(kr[t], oracle.round_f16(ref.rope(k[t], t, nh)))
+        row = ref.attention(oracle.round_f16(ref.rope(q[t], t, nh)), kr[:t + 1], v[:t + 1], nh)
+        assert np.max(np.abs(a[t].astype(np.float64) - row)) <= 1e-3 * max(1.0, np.abs(row).max())
+    # the sequence route fills the caches the way decoding does
+    H2, F2 = 128, 256
+    mats = small_mats(7, H2, F2)
+    X = fq_synth.activations(8, 5, H2)
+    kc, vc = np.zeros((6, H2), np.float16), np.zeros((6, H2), np.float16)
+    ref.sequence_block(X, mats, 1, kc, vc)
+    kd, vd = np.zeros((6, H2), np.float16), np.zeros((6, H2), np.float16)
+    for t in range(5):
+        ref.decode_block(X[t:t + 1], mats, kd, vd, t, 1)
+    assert np.array_equal(kc, kd) and np.array_equal(vc, vd) and not kc[5].any()
+
+
 def test_decode_step_runs_the_blocks_in_order():
     H, F, nh, L = 128, 256, 2, 3
     layers = [small_mats(20 + l, H, F) for l in range(L)]
