@@ -166,7 +166,7 @@ int fq_stack_forward(const fq_layer *layers, int L, const uint8_t *bitvec,
  * All tensors fp16 [M,H] row-major on the device; b and c may be NULL where unused.
  *   op 0: out = rms(a)              op 1: out = rms(a + b + c)
  *   op 2: out = a + b               op 3: out = rms(silu(a) * b)
- *   op 4: out = rms(a + b)
+ *   op 4: out = rms(a + b)          op 5: out = silu(a) * b (no norm: real decoder blocks)
  */
 int fq_glue(int op, const void *a, const void *b, const void *c, int M, int H, void *out, void *stream);
 
@@ -247,6 +247,14 @@ int fq_logit_l2(const void *a, const void *b, int M, int V, float *dist_out, voi
  * Tmax) bytes, 16-byte aligned.  Six launches per block (q/k/v, attention and
  * its merge when pos >= 128, o, gate/up, down), all on `stream`; positions must
  * be fed in order 0, 1, 2, ... for the cache to be complete.
+ *
+ * fq_attn_prefill / fq_prefill_forward: the same blocks over a whole sequence, rows
+ * 0..T-1 of x at positions 0..T-1 (causal attention; Algorithm 1's calibrationEval on
+ * real blocks, and the way to fill the caches before decoding).  q, k, v, out and
+ * x_in, x_out are fp16 [T,H] row-major; the caches as above, positions 0..T-1
+ * written; workspace of fq_attn_prefill_workspace_bytes(T, n_heads) respectively
+ * fq_prefill_workspace_bytes(T, hidden, ffn) bytes.  FQ_ERR_SHAPE unless
+ * 0 < T <= Tmax <= 131072.
  */
 size_t fq_attn_workspace_bytes(int Tmax, int n_heads);
 size_t fq_decode_workspace_bytes(int hidden, int ffn, int Tmax);
@@ -255,6 +263,13 @@ int fq_attn_decode(const void *q, const void *k, const void *v, void *k_cache, v
 int fq_decode_step(const fq_layer *layers, int L, const uint8_t *bitvec, const void *x_in, void *x_out,
                    void *k_cache, void *v_cache, int pos, int Tmax, const float *rope, void *workspace,
                    size_t workspace_bytes, void *stream);
+size_t fq_attn_prefill_workspace_bytes(int T, int n_heads);
+size_t fq_prefill_workspace_bytes(int T, int hidden, int ffn);
+int fq_attn_prefill(const void *q, const void *k, const void *v, int T, void *k_cache, void *v_cache, int Tmax,
+                    int n_heads, const float *rope, void *out, void *workspace, size_t workspace_bytes, void *stream);
+int fq_prefill_forward(const fq_layer *layers, int L, const uint8_t *bitvec, const void *x_in, int T, void *x_out,
+                       void *k_cache, void *v_cache, int Tmax, const float *rope, void *workspace,
+                       size_t workspace_bytes, void *stream);
 
 #ifdef __cplusplus
 }

@@ -70,6 +70,10 @@ def _load() -> ctypes.CDLL:
         "fq_decode_workspace_bytes": (sz, [ci, ci, ci]),
         "fq_attn_decode": (ci, [vp, vp, vp, vp, vp, ci, ci, ci, vp, vp, vp, sz, vp]),
         "fq_decode_step": (ci, [ctypes.POINTER(fq_layer), ci, vp, vp, vp, vp, vp, ci, ci, vp, vp, sz, vp]),
+        "fq_attn_prefill_workspace_bytes": (sz, [ci, ci]),
+        "fq_prefill_workspace_bytes": (sz, [ci, ci, ci]),
+        "fq_attn_prefill": (ci, [vp, vp, vp, ci, vp, vp, ci, ci, vp, vp, vp, sz, vp]),
+        "fq_prefill_forward": (ci, [ctypes.POINTER(fq_layer), ci, vp, vp, ci, vp, vp, vp, ci, vp, vp, sz, vp]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -82,7 +86,8 @@ _lib = _load()
 EXPORTS = ("fq_last_error", "fq_version", "fq_quantize_rtn", "fq_packed_bytes", "fq_meta_count", "fq_pack_groups",
            "fq_dequant", "fq_qlinear", "fq_stack_workspace_bytes", "fq_stack_forward", "fq_glue", "fq_dense_f16",
            "fq_token_nll", "fq_logit_l2", "fq_head_nll_workspace_bytes", "fq_head_nll",
-           "fq_attn_workspace_bytes", "fq_decode_workspace_bytes", "fq_attn_decode", "fq_decode_step")
+           "fq_attn_workspace_bytes", "fq_decode_workspace_bytes", "fq_attn_decode", "fq_decode_step",
+           "fq_attn_prefill_workspace_bytes", "fq_prefill_workspace_bytes", "fq_attn_prefill", "fq_prefill_forward")
 
 
 def _check(rc: int) -> None:
@@ -391,4 +396,62 @@ def fq_decode_step(stack: Stack, bitvec, x, k_cache, v_cache, pos: int, rope, ou
         workspace = torch.empty(fq_decode_workspace_bytes(H, stack.ffn, Tmax), dtype=torch.uint8, device=x.device)
     _check(_lib.fq_decode_step(stack.table, stack.L, _hp(bitvec), _dp(x), _dp(out), _dp(k_cache), _dp(v_cache), pos,
                                Tmax, _dp(rope), _dp(workspace), workspace.numel(), _stream(stream)))
+    return out
+
+
+def fq_attn_prefill_workspace_bytes(T: int, n_heads: int) -> int:
+    return _lib.fq_attn_prefill_workspace_bytes(T, n_heads)
+
+
+def fq_prefill_workspace_bytes(T: int, hidden: int, ffn: int) -> int:
+    return _lib.fq_prefill_workspace_bytes(T, hidden, ffn)
+
+
+def fq_attn_prefill(q, k, v, k_cache, v_cache, rope, out=None, workspace=None, stream=None):
+    """Causal attention over rows 0..T-1 (positions 0..T-1); q, k, v fp16 [T, 128 n_heads]; fills the caches."""
+    torch = _torch()
+    q, k, v = (_dev(t, torch.float16, n) for t, n in ((q, "q"), (k, "k"), (v, "v")))
+    k_cache, v_cache = _dev(k_cache, torch.float16, "k_cache"), _dev(v_cache, torch.float16, "v_cache")
+    rope = _dev(rope, torch.float32, "rope")
+    if k_cache.dim() != 3 or k_cache.shape[2] != 128 or v_cache.shape != k_cache.shape:
+        raise ValueError("fq_attn_prefill: caches [n_heads, Tmax, 128]")
+    n_heads, Tmax, _ = k_cache.shape
+    T, H = q.shape
+    if H != 128 * n_heads or k.shape != q.shape or v.shape != q.shape:
+        raise ValueError("fq_attn_prefill: q, k, v [T, 128 n_heads]")
+    if rope.shape[0] < Tmax or tuple(rope.shape[1:]) != (64, 2):
+        raise ValueError("fq_attn_prefill: rope must be [>=Tmax, 64, 2]")
+    if out is None:
+        out = torch.empty_like(q)
+    if workspace is None:
+        workspace = torch.empty(fq_attn_prefill_workspace_bytes(T, n_heads), dtype=torch.uint8, device=q.device)
+    _check(_lib.fq_attn_prefill(_dp(q), _dp(k), _dp(v), T, _dp(k_cache), _dp(v_cache), Tmax, n_heads, _dp(rope),
+                                _dp(out), _dp(workspace), workspace.numel(), _stream(stream)))
+    return out
+
+
+def fq_prefill_forward(stack: Stack, bitvec, x, k_cache, v_cache, rope, out=None, workspace=None, stream=None):
+    """A whole sequence x [T, hidden] through the stack's blocks as real decoder blocks; caches
+    fp16 [L, n_heads, Tmax, 128], positions 0..T-1 filled."""
+    torch = _torch()
+    x = _dev(x, torch.float16, "x")
+    k_cache, v_cache = _dev(k_cache, torch.float16, "k_cache"), _dev(v_cache, torch.float16, "v_cache")
+    rope = _dev(rope, torch.float32, "rope")
+    bitvec = np.ascontiguousarray(bitvec, dtype=np.uint8)
+    if bitvec.size != 7 * stack.L:
+        raise ValueError("bitvec needs 7 entries per block")
+    if k_cache.dim() != 4 or k_cache.shape[3] != 128 or v_cache.shape != k_cache.shape:
+        raise ValueError("fq_prefill_forward: caches [L, n_heads, Tmax, 128]")
+    L, n_heads, Tmax, _ = k_cache.shape
+    T, H = x.shape
+    if L != stack.L or H != stack.hidden or H != 128 * n_heads:
+        raise ValueError("fq_prefill_forward: x [T, hidden], caches [L, hidden/128, Tmax, 128]")
+    if rope.shape[0] < Tmax or tuple(rope.shape[1:]) != (64, 2):
+        raise ValueError("fq_prefill_forward: rope must be [>=Tmax, 64, 2]")
+    if out is None:
+        out = torch.empty_like(x)
+    if workspace is None:
+        workspace = torch.empty(fq_prefill_workspace_bytes(T, H, stack.ffn), dtype=torch.uint8, device=x.device)
+    _check(_lib.fq_prefill_forward(stack.table, stack.L, _hp(bitvec), _dp(x), T, _dp(out), _dp(k_cache), _dp(v_cache),
+                                   Tmax, _dp(rope), _dp(workspace), workspace.numel(), _stream(stream)))
     return out

@@ -109,8 +109,8 @@ extern "C" int fq_dense_f16(const void *x, int M, const void *W, int N, int K, v
 
 extern "C" int fq_glue(int op, const void *a, const void *b, const void *c, int M, int H, void *out, void *stream)
 {
-    if (op < 0 || op > 4)
-        return fq_fail(FQ_ERR_SHAPE, "fq_glue: op=%d not in 0..4", op);
+    if (op < 0 || op > 5)
+        return fq_fail(FQ_ERR_SHAPE, "fq_glue: op=%d not in 0..5", op);
     if (!a || !out || (op != 0 && !b) || (op == 1 && !c))
         return fq_fail(FQ_ERR_NULL, "fq_glue: NULL argument for op %d", op);
     if (M <= 0 || H <= 0 || H % 8 != 0 || H > kMaxGlueH)
@@ -377,4 +377,108 @@ extern "C" int fq_decode_step(const fq_layer *layers, int L, const uint8_t *bitv
 #undef FQ_STEP
     }
     return check_hip(fq_launch_glue(2, x1, d, nullptr, 1, H, x_out, st), "glue add");
+}
+
+extern "C" size_t fq_attn_prefill_workspace_bytes(int T, int n_heads)
+{
+    if (T <= 0 || n_heads <= 0)
+        return 0;
+    return align_up(fq_attn_prefill_scratch_bytes(T, n_heads));
+}
+
+extern "C" int fq_attn_prefill(const void *q, const void *k, const void *v, int T, void *k_cache, void *v_cache,
+                               int Tmax, int n_heads, const float *rope, void *out, void *workspace,
+                               size_t workspace_bytes, void *stream)
+{
+    if (!q || !k || !v || !k_cache || !v_cache || !rope || !out || !workspace)
+        return fq_fail(FQ_ERR_NULL, "fq_attn_prefill: NULL argument");
+    if (n_heads <= 0 || T <= 0 || T > Tmax || Tmax > fq_attn_max_positions() || !below_4gib(T, (size_t)n_heads * 128, 2))
+        return fq_fail(FQ_ERR_SHAPE, "fq_attn_prefill: n_heads=%d T=%d Tmax=%d (need 0 < T <= Tmax <= %d)", n_heads, T, Tmax,
+                       fq_attn_max_positions());
+    if (workspace_bytes < fq_attn_prefill_workspace_bytes(T, n_heads))
+        return fq_fail(FQ_ERR_WORKSPACE, "fq_attn_prefill: workspace of %zu bytes, need %zu", workspace_bytes,
+                       fq_attn_prefill_workspace_bytes(T, n_heads));
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(k_cache) || !aligned16(v_cache) ||
+        !aligned16(rope) || !aligned16(out) || !aligned16(workspace))
+        return fq_fail(FQ_ERR_ALIGN, "fq_attn_prefill: pointers must be 16-byte aligned");
+    return check_hip(fq_launch_attn_prefill(q, k, v, T, k_cache, v_cache, Tmax, n_heads, rope, out, workspace,
+                                            static_cast<fq_stream>(stream)), "fq_attn_prefill launch");
+}
+
+// Workspace: u, q, k, v, a, o, x1, d, x (hidden wide), g, p, m (ffn wide), then the attention's scratch.
+extern "C" size_t fq_prefill_workspace_bytes(int T, int hidden, int ffn)
+{
+    if (T <= 0 || hidden <= 0 || ffn <= 0 || hidden % 128 != 0)
+        return 0;
+    return 9 * align_up((size_t)T * hidden * 2) + 3 * align_up((size_t)T * ffn * 2) +
+           align_up(fq_attn_prefill_scratch_bytes(T, hidden / 128));
+}
+
+extern "C" int fq_prefill_forward(const fq_layer *layers, int L, const uint8_t *bitvec, const void *x_in, int T,
+                                  void *x_out, void *k_cache, void *v_cache, int Tmax, const float *rope,
+                                  void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!layers || !bitvec || !x_in || !x_out || !k_cache || !v_cache || !rope || !workspace)
+        return fq_fail(FQ_ERR_NULL, "fq_prefill_forward: NULL argument");
+    if (L <= 0 || T <= 0 || T > Tmax || Tmax > fq_attn_max_positions())
+        return fq_fail(FQ_ERR_SHAPE, "fq_prefill_forward: L=%d T=%d Tmax=%d (need 0 < T <= Tmax <= %d)", L, T, Tmax,
+                       fq_attn_max_positions());
+    int H = 0, F = 0;
+    if (int rc = validate_layers("fq_prefill_forward", layers, L, bitvec, &H, &F))
+        return rc;
+    if (workspace_bytes < fq_prefill_workspace_bytes(T, H, F))
+        return fq_fail(FQ_ERR_WORKSPACE, "fq_prefill_forward: workspace of %zu bytes, need %zu", workspace_bytes,
+                       fq_prefill_workspace_bytes(T, H, F));
+    if (!aligned16(x_in) || !aligned16(x_out) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(rope) ||
+        !aligned16(workspace))
+        return fq_fail(FQ_ERR_ALIGN, "fq_prefill_forward: pointers must be 16-byte aligned");
+
+    fq_stream st = static_cast<fq_stream>(stream);
+    const int n_heads = H / 128, M = T;
+    const size_t hb = align_up((size_t)T * H * 2), fb = align_up((size_t)T * F * 2), layer_cache = (size_t)Tmax * H * 2;
+    char *ws = static_cast<char *>(workspace);
+    void *u = ws, *q = ws + hb, *k = ws + 2 * hb, *v = ws + 3 * hb, *a = ws + 4 * hb, *o = ws + 5 * hb,
+         *x1 = ws + 6 * hb, *d = ws + 7 * hb, *xc = ws + 8 * hb;
+    void *g = ws + 9 * hb, *p = ws + 9 * hb + fb, *mm = ws + 9 * hb + 2 * fb, *attn = ws + 9 * hb + 3 * fb;
+    fq_packed_ref sel[7];
+    const void *xcur = x_in;
+    for (int l = 0; l < L; ++l) {
+        for (int j = 0; j < 7; ++j) {
+            const fq_matrix &mx = layers[l].m[j];
+            const int bits = bitvec[7 * l + j], bi = fq_bits_index(bits);
+            sel[j] = fq_packed_ref{mx.packed[bi], mx.scales[bi], mx.zeros[bi], mx.N, mx.K, bits};
+        }
+        void *xnext = (l == L - 1) ? x_out : xc;
+        void *const qkv[3] = {q, k, v};
+        void *const gp[2] = {g, p};
+        int rc;
+#define FQ_STEP(call) \
+    if ((rc = (call)) != FQ_OK) \
+        return rc
+        FQ_STEP(check_hip(fq_launch_glue(0, xcur, nullptr, nullptr, M, H, u, st), "glue rms"));
+        if (M > 16) {
+            FQ_STEP(qlinear_multi_checked(u, M, &sel[0], qkv, 3, st));
+        } else {
+            for (int j = 0; j < 3; ++j)
+                FQ_STEP(qlinear_checked(u, M, sel[j], qkv[j], st));
+        }
+        FQ_STEP(check_hip(fq_launch_attn_prefill(q, k, v, T, static_cast<char *>(k_cache) + l * layer_cache,
+                                                 static_cast<char *>(v_cache) + l * layer_cache, Tmax, n_heads, rope, a,
+                                                 attn, st), "prefill attention"));
+        FQ_STEP(qlinear_checked(a, M, sel[3], o, st));
+        FQ_STEP(check_hip(fq_launch_glue(2, xcur, o, nullptr, M, H, x1, st), "glue add"));
+        FQ_STEP(check_hip(fq_launch_glue(0, x1, nullptr, nullptr, M, H, u, st), "glue rms"));
+        if (M > 16) {
+            FQ_STEP(qlinear_multi_checked(u, M, &sel[4], gp, 2, st));
+        } else {
+            for (int j = 0; j < 2; ++j)
+                FQ_STEP(qlinear_checked(u, M, sel[4 + j], gp[j], st));
+        }
+        FQ_STEP(check_hip(fq_launch_glue(5, g, p, nullptr, M, F, mm, st), "glue silu*mul"));
+        FQ_STEP(qlinear_checked(mm, M, sel[6], d, st));
+        FQ_STEP(check_hip(fq_launch_glue(2, x1, d, nullptr, M, H, xnext, st), "glue add"));
+#undef FQ_STEP
+        xcur = xnext;
+    }
+    return FQ_OK;
 }

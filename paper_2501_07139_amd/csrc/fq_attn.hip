@@ -225,3 +225,236 @@ int fq_launch_attn_decode(const void *q, const void *k, const void *v, void *k_c
     hipLaunchKernelGGL(attn_merge_kernel, dim3(n_heads), dim3(AD), 0, st, a);
     return (int)hipGetLastError();
 }
+
+// ------------------------------------------------------------------ prefill
+// Causal attention over a whole sequence (positions 0..T-1 of one sequence), for running real decoder blocks
+// over calibration sequences (Algorithm 1, calibrationEval) and for filling the cache before decoding.
+//
+// attn_prep_kernel, per (64 positions, head): rotates q (to a scratch array, row-major like q) and k (into
+// the head-major key cache), copies v into the value cache and also writes it transposed, [head][128][Tp],
+// through an LDS tile, so that the second product below finds the positions of one dimension contiguous.
+//
+// attn_prefill_kernel, per (64 query rows, head), 4 wavefronts x 16 query rows, over the key/value tiles of
+// 64 positions up to the diagonal, both copied straight into double-buffered LDS tiles:
+//   S^T = K . Q'^T     16x16x32 MFMA, A = key rows from LDS, B = the wavefront's query rows (registers)
+//   a lane then holds scores of ONE query row (column l%16): running max and sum need only in-lane work and
+//   two cross-lane steps; P = exp(S - max) rounded to fp16 is, as it stands in the lane, the B operand of
+//   O^T = V^T . P^T    A = rows of the transposed values from LDS (the k index runs over the positions in
+//   the order the score blocks left them: 4g..4g+3 of one block, then of the next),
+// with the accumulators rescaled per lane when the maximum moves.  Heavy query tiles are launched first.
+namespace {
+
+constexpr int PT = 64; // positions per tile, queries and keys alike
+
+struct PrefillArgs {
+    const _Float16 *q, *k, *v; // [T][H]
+    _Float16 *qr;              // [T][H] rotated queries
+    _Float16 *kc, *vc;         // [heads][Tmax][128]
+    _Float16 *vt;              // [heads][128][Tp]
+    const float *rope;         // [Tmax][64][2]
+    _Float16 *out;             // [T][H]
+    int T, Tp, Tmax, H;
+};
+
+__global__ __launch_bounds__(256) void attn_prep_kernel(PrefillArgs p)
+{
+    __shared__ _Float16 vs[PT][AD + 2]; // +2 halves: the column reads below spread over the banks
+    const int t0 = blockIdx.x * PT, head = blockIdx.y, tid = threadIdx.x;
+    for (int c = tid; c < PT * 16; c += 256) {
+        const int row = c >> 4, r = c & 15, t = t0 + row;
+        h8 vv = {};
+        if (t < p.T) {
+            const size_t src = (size_t)t * p.H + (size_t)head * AD + 8 * r;
+            const f4 lo = *reinterpret_cast<const f4 *>(p.rope + (size_t)t * AD + 8 * r);
+            const f4 hi = *reinterpret_cast<const f4 *>(p.rope + (size_t)t * AD + 8 * r + 4);
+            const float cs[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+            *reinterpret_cast<h8 *>(p.qr + src) = rope8(*reinterpret_cast<const h8 *>(p.q + src), cs);
+            const size_t dst = ((size_t)head * p.Tmax + t) * AD + 8 * r;
+            *reinterpret_cast<h8 *>(p.kc + dst) = rope8(*reinterpret_cast<const h8 *>(p.k + src), cs);
+            vv = *reinterpret_cast<const h8 *>(p.v + src);
+            *reinterpret_cast<h8 *>(p.vc + dst) = vv;
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+            vs[row][8 * r + e] = vv[e]; // zeros past T: they meet zero weights, and 0 * 0 stays 0
+    }
+    __syncthreads();
+    for (int c = tid; c < AD * (PT / 8); c += 256) {
+        const int d = c >> 3, j = c & 7;
+        h8 o;
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+            o[e] = vs[8 * j + e][d];
+        *reinterpret_cast<h8 *>(p.vt + ((size_t)head * AD + d) * p.Tp + t0 + 8 * j) = o;
+    }
+}
+
+__global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillArgs p)
+{
+    __shared__ h8 Ks[2][PT * 16];  // chunk ch of key row r at r*16 + (ch ^ (r & 15))
+    __shared__ h8 Vs[2][AD * 8];   // 16-byte slot sl of dimension row d at d*8 + (sl ^ ((d >> 1) & 7))
+
+    const int qt = (int)gridDim.x - 1 - (int)blockIdx.x, head = blockIdx.y; // long rows of tiles first
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int col = lane & 15, g = lane >> 4;
+    const int q0 = qt * PT + 16 * wave;
+
+    // the wavefront's query rows as B operands of the four k-steps over the head dimension
+    h8 qb[4];
+    {
+        const size_t row = (size_t)min(q0 + col, p.T - 1) * p.H + (size_t)head * AD + 8 * g;
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+            qb[s] = *reinterpret_cast<const h8 *>(p.qr + row + 32 * s);
+    }
+
+    const fq_rsrc kr = make_rsrc(p.kc + (size_t)head * p.Tmax * AD, (uint32_t)p.Tmax * AD * 2u);
+    const fq_rsrc vr = make_rsrc(p.vt + (size_t)head * AD * p.Tp, (uint32_t)AD * (uint32_t)p.Tp * 2u);
+    // copies: the i-th of a wavefront fills the 64 slots from 64*(wave + 4i) of a tile
+    uint32_t koff[4], voff[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int krow = 4 * (wave + 4 * i) + (lane >> 4), kch = (lane & 15) ^ (krow & 15);
+        koff[i] = ((uint32_t)krow * AD + (uint32_t)kch * 8u) * 2u; // + tile * 64 rows, clamped below
+        const int vrow = 8 * (wave + 4 * i) + (lane >> 3), vsl = (lane & 7) ^ ((vrow >> 1) & 7);
+        voff[i] = ((uint32_t)vrow * (uint32_t)p.Tp + (uint32_t)vsl * 8u) * 2u;
+    }
+    auto copy_tiles = [&](int buffer, int jt) {
+        // key rows past the last position re-read the last one: their scores are masked
+        const int last = p.T - 1 - jt * PT;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int krow = 4 * (wave + 4 * i) + (lane >> 4);
+            const uint32_t off = krow <= last ? koff[i] : koff[i] - (uint32_t)(krow - last) * (AD * 2u);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(kr, &Ks[buffer][64 * (wave + 4 * i)], 16, off,
+                                                     (uint32_t)jt * (PT * AD * 2u), 0, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(vr, &Vs[buffer][64 * (wave + 4 * i)], 16, voff[i],
+                                                     (uint32_t)jt * (PT * 2u), 0, 0);
+    };
+
+    f4 acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+        acc[i] = f4{0.f, 0.f, 0.f, 0.f};
+    float mx = -INFINITY, l = 0.f;
+
+    copy_tiles(0, 0);
+    __builtin_amdgcn_s_waitcnt(FQ_WAIT_VMCNT0);
+    __syncthreads();
+
+    for (int jt = 0; jt <= qt; ++jt) {
+        const int cur = jt & 1;
+        if (jt < qt)
+            copy_tiles(cur ^ 1, jt + 1);
+
+        // scores of 64 positions against the wavefront's 16 query rows, transposed
+        f4 st[4];
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            st[b] = f4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                const int row = 16 * b + col, ch = 4 * s + g;
+                st[b] = mfma16x16x32(Ks[cur][row * 16 + (ch ^ (row & 15))], qb[s], st[b]);
+            }
+        }
+        // lane: query row q0 + col, positions jt*64 + 16b + 4g + v
+        float tmax = -INFINITY;
+#pragma unroll
+        for (int b = 0; b < 4; ++b)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int kv = jt * PT + 16 * b + 4 * g + v;
+                const float sc = st[b][v] * 0.08838834764831845f; // 1 / sqrt(128)
+                st[b][v] = kv <= q0 + col ? sc : -INFINITY;      // causal mask (also hides positions past T)
+                tmax = fmaxf(tmax, st[b][v]);
+            }
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+        const float mnew = fmaxf(mx, tmax); // finite from the first tile on: position 0 is visible to every row
+        const float alpha = __expf(mx - mnew);
+        mx = mnew;
+        h8 pb[2];
+        float psum = 0.f;
+#pragma unroll
+        for (int b = 0; b < 4; ++b)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const float e = __expf(st[b][v] - mnew);
+                psum += e;
+                pb[b >> 1][4 * (b & 1) + v] = (_Float16)e;
+            }
+        l = l * alpha + psum;
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            acc[i] *= alpha;
+        // O^T += V^T . P^T; k-slot e of k-step ks is position 32ks + 4g + e (e < 4) or 32ks + 16 + 4g + e - 4
+#pragma unroll
+        for (int db = 0; db < 8; ++db) {
+            const int d = 16 * db + col, sw = (d >> 1) & 7;
+            const uint2 *rowp = reinterpret_cast<const uint2 *>(&Vs[cur][d * 8]);
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks) {
+                const int s0 = 4 * ks + (g >> 1), s1 = s0 + 2;
+                const uint2 lo = rowp[2 * (s0 ^ sw) + (g & 1)], hi = rowp[2 * (s1 ^ sw) + (g & 1)];
+                const u4v both = {lo.x, lo.y, hi.x, hi.y};
+                acc[db] = mfma16x16x32(__builtin_bit_cast(h8, both), pb[ks], acc[db]);
+            }
+        }
+        __builtin_amdgcn_s_waitcnt(FQ_WAIT_VMCNT0);
+        __syncthreads();
+    }
+
+    l += __shfl_xor(l, 16, 64);
+    l += __shfl_xor(l, 32, 64);
+    const int q = q0 + col;
+    if (q < p.T) {
+        const float inv = 1.0f / l;
+#pragma unroll
+        for (int db = 0; db < 8; ++db) {
+            const h4 o = {(_Float16)(acc[db][0] * inv), (_Float16)(acc[db][1] * inv), (_Float16)(acc[db][2] * inv),
+                          (_Float16)(acc[db][3] * inv)};
+            *reinterpret_cast<h4 *>(p.out + (size_t)q * p.H + (size_t)head * AD + 16 * db + 4 * g) = o;
+        }
+    }
+}
+
+} // namespace
+
+static int prefill_tp(int T) { return (T + PT - 1) / PT * PT; }
+
+size_t fq_attn_prefill_scratch_bytes(int T, int n_heads)
+{
+    return (size_t)T * n_heads * AD * 2 + (size_t)n_heads * AD * prefill_tp(T) * 2;
+}
+
+// Shapes validated by the caller: 0 < T <= Tmax, head dimension 128, 16-byte aligned pointers, the byte
+// sizes of one head's cache and of one head's transposed values below 4 GiB.
+int fq_launch_attn_prefill(const void *q, const void *k, const void *v, int T, void *k_cache, void *v_cache,
+                           int Tmax, int n_heads, const float *rope, void *out, void *workspace, fq_stream st)
+{
+    PrefillArgs a;
+    a.q = static_cast<const _Float16 *>(q);
+    a.k = static_cast<const _Float16 *>(k);
+    a.v = static_cast<const _Float16 *>(v);
+    a.qr = static_cast<_Float16 *>(workspace);
+    a.vt = a.qr + (size_t)T * n_heads * AD;
+    a.kc = static_cast<_Float16 *>(k_cache);
+    a.vc = static_cast<_Float16 *>(v_cache);
+    a.rope = rope;
+    a.out = static_cast<_Float16 *>(out);
+    a.T = T;
+    a.Tp = prefill_tp(T);
+    a.Tmax = Tmax;
+    a.H = n_heads * AD;
+    const int tiles = a.Tp / PT;
+    hipLaunchKernelGGL(attn_prep_kernel, dim3(tiles, n_heads), dim3(256), 0, st, a);
+    int rc = (int)hipGetLastError();
+    if (rc != 0)
+        return rc;
+    hipLaunchKernelGGL(attn_prefill_kernel, dim3(tiles, n_heads), dim3(256), 0, st, a);
+    return (int)hipGetLastError();
+}

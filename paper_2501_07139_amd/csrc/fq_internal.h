@@ -53,6 +53,11 @@ size_t fq_attn_scratch_bytes(int Tmax, int n_heads);
 int fq_attn_max_positions(); // largest Tmax the merge of the splits handles
 int fq_launch_attn_decode(const void *q, const void *k, const void *v, void *k_cache, void *v_cache, int pos,
                           int Tmax, int n_heads, const float *rope, void *out, void *workspace, fq_stream st);
+// Causal attention over positions 0..T-1 of one sequence: rotates q and k, fills the caches, writes out
+// [T,H].  Workspace of fq_attn_prefill_scratch_bytes(T, n_heads) bytes.
+size_t fq_attn_prefill_scratch_bytes(int T, int n_heads);
+int fq_launch_attn_prefill(const void *q, const void *k, const void *v, int T, void *k_cache, void *v_cache,
+                           int Tmax, int n_heads, const float *rope, void *out, void *workspace, fq_stream st);
 int fq_launch_glue(int op, const void *a, const void *b, const void *c, int M, int H, void *out, fq_stream st);
 int fq_launch_nll(const void *logits, const int32_t *labels, int M, int V, float *nll, fq_stream st);
 int fq_launch_logit_l2(const void *a, const void *b, int M, int V, float *dist, fq_stream st);

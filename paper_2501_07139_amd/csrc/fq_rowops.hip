@@ -68,7 +68,7 @@ __global__ __launch_bounds__(256) void glue_kernel(const _Float16 *__restrict__ 
         }
     }
     float inv = 1.0f;
-    if constexpr (OP != 2) {
+    if constexpr (OP != 2 && OP != 5) { // 2 and 5 have no norm
         __shared__ float part[4];
         ss = wave_sum(ss);
         if ((threadIdx.x & 63) == 0)
@@ -193,7 +193,8 @@ int fq_launch_glue(int op, const void *a, const void *b, const void *c, int M, i
     case 1: hipLaunchKernelGGL(glue_kernel<1>, grid, block, 0, st, pa, pb, pc, H, po); break;
     case 2: hipLaunchKernelGGL(glue_kernel<2>, grid, block, 0, st, pa, pb, pc, H, po); break;
     case 3: hipLaunchKernelGGL(glue_kernel<3>, grid, block, 0, st, pa, pb, pc, H, po); break;
-    default: hipLaunchKernelGGL(glue_kernel<4>, grid, block, 0, st, pa, pb, pc, H, po); break;
+    case 4: hipLaunchKernelGGL(glue_kernel<4>, grid, block, 0, st, pa, pb, pc, H, po); break;
+    default: hipLaunchKernelGGL(glue_kernel<5>, grid, block, 0, st, pa, pb, pc, H, po); break;
     }
     return (int)hipGetLastError();
 }

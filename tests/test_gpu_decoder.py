@@ -55,8 +55,11 @@ def ulps(a, b):
 
 
 def rel_err(y, r):
-    y, r = y.astype(np.float64), r.astype(np.float64)
-    return float(np.max(np.abs(y - r)) / max(np.sqrt(np.mean(r * r)), 1e-30))
+    """max |y - r| / max(|r|, rms of r's row): the element-wise relative error, with the row's scale as the
+    floor where r is near zero (the same reading as for the linears)."""
+    y, r = np.atleast_2d(y.astype(np.float64)), np.atleast_2d(r.astype(np.float64))
+    rms = np.sqrt(np.mean(r * r, axis=1, keepdims=True))
+    return float(np.max(np.abs(y - r) / np.maximum(np.maximum(np.abs(r), rms), 1e-30)))
 
 
 @pytest.mark.parametrize("case", [(4, 300, (0, 1, 15, 16, 127, 128, 129, 255, 256, 299)), (32, 2048, (2047,)),
@@ -194,3 +197,75 @@ def test_decode_step_refuses_bad_arguments(fq, torch):
     with pytest.raises(fq.FqError):
         fq.fq_decode_step(stack, bad, x, kc, kc.clone(), 0, rope)
     torch.cuda.synchronize()
+
+
+# --------------------------------------------------------------------- prefill
+@pytest.mark.parametrize("case", [(2, 1, 8), (2, 63, 64), (2, 64, 64), (2, 65, 200), (4, 200, 256), (32, 2048, 2048)], ids=str)
+def test_attn_prefill_against_oracle(fq, torch, case):
+    """Causal attention over a whole sequence against the masked T x T product of the oracle (full sequence
+    for short ones, a sample of rows through the decode form for the long one); caches as after decoding."""
+    n_heads, T, Tmax = case
+    H = 128 * n_heads
+    rng = np.random.default_rng(9)
+    q = (rng.normal(size=(T, H)) * 1.5).astype(np.float16)
+    k = rng.normal(size=(T, H)).astype(np.float16)
+    v = rng.normal(size=(T, H)).astype(np.float16)
+    rope = fq.rope_table(Tmax)
+    kc = torch.full((n_heads, Tmax, 128), float("nan"), dtype=torch.float16, device="cuda")
+    vc = torch.full_like(kc, float("nan"))
+    got = host16(fq.fq_attn_prefill(dev(torch, q), dev(torch, k), dev(torch, v), kc, vc, rope))
+    gK, gV = from_heads(host16(kc)), from_heads(host16(vc))
+    assert np.array_equal(gV[:T].view(np.uint16), v.view(np.uint16))
+    assert np.isnan(gK[T:].astype(np.float32)).all() and np.isnan(gV[T:].astype(np.float32)).all()  # rows past T untouched
+    if T <= 256:
+        want, kr = ref.sequence_attention(q, k, v, n_heads)
+        assert rel_err(got, want) <= 2e-3
+        d = ulps(gK[:T], kr)
+        assert d.max() <= 1 and np.mean(d == 0) > 0.98
+    else:
+        rows = [0, 1, 63, 64, 65, 1000, 1023, 1024, T - 2, T - 1]
+        kr = oracle.round_f16(np.stack([ref.rope(k[t], t, n_heads) for t in range(T)]))
+        # one fp16 step of the result, or (where the rotation cancels to almost nothing) of the fp32 terms
+        dk = np.abs(gK[:T].astype(np.float64) - kr.astype(np.float64))
+        assert np.all(dk <= 1e-3 * np.abs(kr.astype(np.float64)) + 2e-6)
+        for t in rows:
+            want = ref.attention(oracle.round_f16(ref.rope(q[t], t, n_heads)), kr[:t + 1], v[:t + 1], n_heads)
+            assert rel_err(got[t], want) <= 2e-3, t
+
+
+def test_prefill_forward_against_oracle_and_decode_continues_from_it(fq, torch):
+    stack, host, sh = build_real_stack(fq, 830)
+    L, H, nh, Tmax, T = sh["layers"], sh["hidden"], sh["hidden"] // 128, 160, 150
+    bitvec = fq_synth.bit_vector(831, 7 * L, probs=(0.25, 0.25, 0.25, 0.25))
+    mats = [[host[l][j][int(bitvec[7 * l + j])] for j in range(7)] for l in range(L)]
+    rope = fq.rope_table(Tmax)
+    X = fq_synth.activations(832, T + 1, H)
+    kc = torch.zeros((L, nh, Tmax, 128), dtype=torch.float16, device="cuda")
+    vc = torch.zeros_like(kc)
+    got = host16(fq.fq_prefill_forward(stack, bitvec, dev(torch, X[:T]), kc, vc, rope))
+    okc, ovc = np.zeros((L, Tmax, H), np.float16), np.zeros((L, Tmax, H), np.float16)
+    want = ref.sequence_stack(X[:T], mats, nh, okc, ovc).astype(np.float64)
+    diff = np.abs(got.astype(np.float64) - want)
+    scale = np.sqrt(np.mean(want ** 2))
+    assert diff.max() / scale <= 2e-2 and diff.mean() / scale <= 2e-3
+    assert np.max(np.abs(from_heads(host16(kc)).astype(np.float64) - okc.astype(np.float64))) <= 3e-2
+    assert np.max(np.abs(from_heads(host16(vc)).astype(np.float64) - ovc.astype(np.float64))) <= 3e-2
+    # the next token decodes from the prefilled caches like from caches filled token by token
+    nxt = host16(fq.fq_decode_step(stack, bitvec, dev(torch, X[T]), kc, vc, T, rope))
+    kc2, vc2 = torch.zeros_like(kc), torch.zeros_like(vc)
+    for pos in range(T + 1):
+        step = host16(fq.fq_decode_step(stack, bitvec, dev(torch, X[pos]), kc2, vc2, pos, rope))
+    d2 = np.abs(nxt.astype(np.float64) - step.astype(np.float64))
+    assert d2.max() <= 2e-2 * max(1.0, np.abs(step.astype(np.float64)).max()) and d2.mean() <= 2e-3
+    # a short sequence (at most 16 rows) takes the small-M linears
+    short = host16(fq.fq_prefill_forward(stack, bitvec, dev(torch, X[:5]), torch.zeros_like(kc), torch.zeros_like(vc), rope))
+    w5 = ref.sequence_stack(X[:5], mats, nh).astype(np.float64)
+    assert np.max(np.abs(short.astype(np.float64) - w5)) / np.sqrt(np.mean(w5 ** 2)) <= 2e-2
+
+
+def test_glue_silu_mul_without_norm(fq, torch):
+    g = fq_synth.activations(840, 3, 640)
+    p = fq_synth.activations(841, 3, 640)
+    got = host16(fq.fq_glue(5, dev(torch, g), dev(torch, p)))
+    want = oracle.round_f16(oracle.silu_mul(g, p))
+    assert ulps(got, want).max() <= 1 and np.mean(got.view(np.uint16) == want.view(np.uint16)) > 0.98

@@ -123,6 +123,11 @@ def test_error_codes_without_launching_anything():
     assert fq.fq_attn_workspace_bytes(128, 2) >= 2 * 1 * 130 * 4 and fq.fq_attn_workspace_bytes(129, 2) >= 2 * 2 * 130 * 4
     assert fq.fq_decode_workspace_bytes(256, 640, 128) >= 8 * 512 + 2 * 1280 + fq.fq_attn_workspace_bytes(128, 2)
     assert fq.fq_decode_workspace_bytes(200, 640, 128) == 0
+    assert lib.fq_attn_prefill(None, 16, 16, 4, 16, 16, 8, 2, 16, 16, 16, 1 << 24, None) == -1
+    assert lib.fq_attn_prefill(16, 16, 16, 9, 16, 16, 8, 2, 16, 16, 16, 1 << 24, None) == -2     # T > Tmax
+    assert lib.fq_attn_prefill(16, 16, 16, 4, 16, 16, 8, 2, 16, 16, 16, 8, None) == -6
+    assert fq.fq_attn_prefill_workspace_bytes(65, 2) >= 65 * 256 * 2 + 256 * 128 * 2
+    assert fq.fq_prefill_workspace_bytes(0, 256, 640) == 0 and fq.fq_prefill_workspace_bytes(4, 200, 640) == 0
     assert lib.fq_glue(9, 16, 16, 16, 1, 128, 16, None) == -2
     assert lib.fq_dense_f16(16, 1, 16, 1, 100, 16, None) == -2
     # the matrix-core kernels address their arrays through 32-bit offsets: 4 GiB of activations is refused
