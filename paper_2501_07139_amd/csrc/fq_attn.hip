@@ -15,6 +15,8 @@
 #include "fq_device.h"
 #include "fq_internal.h"
 
+#include <type_traits>
+
 namespace {
 
 constexpr int AD = 128;       // head dimension
@@ -234,14 +236,15 @@ int fq_launch_attn_decode(const void *q, const void *k, const void *v, void *k_c
 // the head-major key cache), copies v into the value cache and also writes it transposed, [head][128][Tp],
 // through an LDS tile, so that the second product below finds the positions of one dimension contiguous.
 //
-// attn_prefill_kernel, per (64 query rows, head), 4 wavefronts x 16 query rows, over the key/value tiles of
-// 64 positions up to the diagonal, both copied straight into double-buffered LDS tiles:
+// attn_prefill_kernel, per (128 query rows, head), 4 wavefronts x 2 blocks of 16 query rows, over the
+// key/value tiles of 64 positions up to the diagonal, in double-buffered LDS tiles:
 //   S^T = K . Q'^T     16x16x32 MFMA, A = key rows from LDS, B = the wavefront's query rows (registers)
 //   a lane then holds scores of ONE query row (column l%16): running max and sum need only in-lane work and
 //   two cross-lane steps; P = exp(S - max) rounded to fp16 is, as it stands in the lane, the B operand of
-//   O^T = V^T . P^T    A = rows of the transposed values from LDS (the k index runs over the positions in
-//   the order the score blocks left them: 4g..4g+3 of one block, then of the next),
-// with the accumulators rescaled per lane when the maximum moves.  Heavy query tiles are launched first.
+//   O^T = V^T . P^T    A = rows of the transposed values from LDS (the key rows are dealt to the score
+//   blocks in such an order that a lane's eight weights of a k-step belong to eight contiguous positions),
+// with the accumulators rescaled per lane when the maximum moves.  Long and short query tiles are paired
+// on a CU through the order of the grid.
 namespace {
 
 constexpr int PT = 64; // positions per tile, queries and keys alike
@@ -253,7 +256,7 @@ struct PrefillArgs {
     _Float16 *vt;              // [heads][128][Tp]
     const float *rope;         // [Tmax][64][2]
     _Float16 *out;             // [T][H]
-    int T, Tp, Tmax, H;
+    int T, Tp, Tmax, H, NQ, heads;
 };
 
 __global__ __launch_bounds__(256) void attn_prep_kernel(PrefillArgs p)
@@ -289,23 +292,47 @@ __global__ __launch_bounds__(256) void attn_prep_kernel(PrefillArgs p)
     }
 }
 
+constexpr int QB = 2;            // blocks of 16 query rows per wavefront
+constexpr int QT = 4 * 16 * QB;  // query rows per workgroup
+
+// row of the key tile that feeds row r of score block b: chosen so that the eight positions a lane ends up
+// holding for one k-step of the second product, (4g..4g+3 of blocks 2ks and 2ks+1), are the contiguous
+// positions 32ks + 8g .. + 7, i.e. one 16-byte slot of a transposed value row
+__device__ __forceinline__ int key_row(int b, int r) { return 32 * (b >> 1) + 8 * (r >> 2) + 4 * (b & 1) + (r & 3); }
+// position of 16-byte chunk ch in key row `row`: the sixteen rows a block's operand read touches differ in
+// bits 0-1 and 3-4 of the row number
+__device__ __forceinline__ int key_slot(int row, int ch) { return row * 16 + (ch ^ ((row & 3) | ((row >> 1) & 12))); }
+
 __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillArgs p)
 {
-    __shared__ h8 Ks[2][PT * 16];  // chunk ch of key row r at r*16 + (ch ^ (r & 15))
-    __shared__ h8 Vs[2][AD * 8];   // 16-byte slot sl of dimension row d at d*8 + (sl ^ ((d >> 1) & 7))
+    // Key tiles [64 positions][16 chunks] (see key_slot); value tiles: 16-byte slot sl (eight positions) of
+    // dimension row d at d*8 + (sl ^ ((d >> 1) & 7)).  Two of each, as separate arrays named statically in
+    // a loop unrolled by two: the compiler then knows that the key tile being read is not the one the
+    // copies in flight write, and does not wait for those copies before the first read.  It keeps track of
+    // only a few such copies, so the value tiles take the other road: global memory to registers at the
+    // top of a step, registers to LDS at its end.
+    __shared__ h8 Ks0[PT * 16], Ks1[PT * 16];
+    __shared__ h8 Vs0[AD * 8], Vs1[AD * 8];
 
-    const int qt = (int)gridDim.x - 1 - (int)blockIdx.x, head = blockIdx.y; // long rows of tiles first
+    // Jobs (query tile, head) sorted by length, longest first, are dealt so that the first half of the grid
+    // takes them from the long end and the second half from the short end: the workgroups b and b + half,
+    // which share a CU when the grid is two workgroups per CU, then have about the same total length.
+    const int jobs = (int)gridDim.x, half = (jobs + 1) >> 1, bidx = (int)blockIdx.x;
+    const int job = bidx < half ? bidx : jobs - 1 - (bidx - half);
+    const int qt = p.NQ - 1 - job / p.heads, head = job % p.heads;
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int col = lane & 15, g = lane >> 4;
-    const int q0 = qt * PT + 16 * wave;
+    const int q0 = qt * QT + 16 * QB * wave; // first query row of this wavefront
+    const int last_tile = min((qt * QT + QT - 1) / PT, p.Tp / PT - 1);
 
     // the wavefront's query rows as B operands of the four k-steps over the head dimension
-    h8 qb[4];
-    {
-        const size_t row = (size_t)min(q0 + col, p.T - 1) * p.H + (size_t)head * AD + 8 * g;
+    h8 qb[QB][4];
+#pragma unroll
+    for (int qi = 0; qi < QB; ++qi) {
+        const size_t row = (size_t)min(q0 + 16 * qi + col, p.T - 1) * p.H + (size_t)head * AD + 8 * g;
 #pragma unroll
         for (int s = 0; s < 4; ++s)
-            qb[s] = *reinterpret_cast<const h8 *>(p.qr + row + 32 * s);
+            qb[qi][s] = *reinterpret_cast<const h8 *>(p.qr + row + 32 * s);
     }
 
     const fq_rsrc kr = make_rsrc(p.kc + (size_t)head * p.Tmax * AD, (uint32_t)p.Tmax * AD * 2u);
@@ -314,110 +341,169 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillArgs p)
     uint32_t koff[4], voff[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        const int krow = 4 * (wave + 4 * i) + (lane >> 4), kch = (lane & 15) ^ (krow & 15);
-        koff[i] = ((uint32_t)krow * AD + (uint32_t)kch * 8u) * 2u; // + tile * 64 rows, clamped below
+        const int krow = 4 * (wave + 4 * i) + (lane >> 4);
+        const int kch = (lane & 15) ^ ((krow & 3) | ((krow >> 1) & 12));
+        koff[i] = ((uint32_t)krow * AD + (uint32_t)kch * 8u) * 2u;
         const int vrow = 8 * (wave + 4 * i) + (lane >> 3), vsl = (lane & 7) ^ ((vrow >> 1) & 7);
         voff[i] = ((uint32_t)vrow * (uint32_t)p.Tp + (uint32_t)vsl * 8u) * 2u;
     }
-    auto copy_tiles = [&](int buffer, int jt) {
-        // key rows past the last position re-read the last one: their scores are masked
-        const int last = p.T - 1 - jt * PT;
+    h8 vreg[4];
+    auto load_tiles = [&](h8 *Kdst, int jt) {
+        if (jt * PT + PT <= p.T) { // uniform: only the sequence's last tile can reach past its end
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int krow = 4 * (wave + 4 * i) + (lane >> 4);
-            const uint32_t off = krow <= last ? koff[i] : koff[i] - (uint32_t)(krow - last) * (AD * 2u);
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(kr, &Ks[buffer][64 * (wave + 4 * i)], 16, off,
-                                                     (uint32_t)jt * (PT * AD * 2u), 0, 0);
+            for (int i = 0; i < 4; ++i)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(kr, &Kdst[64 * (wave + 4 * i)], 16, koff[i],
+                                                         (uint32_t)jt * (PT * AD * 2u), 0, 0);
+        } else { // key rows past the last position re-read the last one: their scores are masked
+            const int last = p.T - 1 - jt * PT;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int krow = 4 * (wave + 4 * i) + (lane >> 4);
+                const uint32_t off = krow <= last ? koff[i] : koff[i] - (uint32_t)(krow - last) * (AD * 2u);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(kr, &Kdst[64 * (wave + 4 * i)], 16, off,
+                                                         (uint32_t)jt * (PT * AD * 2u), 0, 0);
+            }
         }
 #pragma unroll
         for (int i = 0; i < 4; ++i)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(vr, &Vs[buffer][64 * (wave + 4 * i)], 16, voff[i],
-                                                     (uint32_t)jt * (PT * 2u), 0, 0);
+            vreg[i] = __builtin_bit_cast(h8, buf_load_b128(vr, voff[i], (uint32_t)jt * (PT * 2u)));
+    };
+    auto store_values = [&](h8 *Vdst) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            Vdst[64 * (wave + 4 * i) + lane] = vreg[i];
     };
 
-    f4 acc[8];
+    f4 acc[QB][8];
+    float mx[QB], l[QB];
 #pragma unroll
-    for (int i = 0; i < 8; ++i)
-        acc[i] = f4{0.f, 0.f, 0.f, 0.f};
-    float mx = -INFINITY, l = 0.f;
+    for (int qi = 0; qi < QB; ++qi) {
+        mx[qi] = -INFINITY;
+        l[qi] = 0.f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            acc[qi][i] = f4{0.f, 0.f, 0.f, 0.f};
+    }
 
-    copy_tiles(0, 0);
+    load_tiles(Ks0, 0);
+    store_values(Vs0);
     __builtin_amdgcn_s_waitcnt(FQ_WAIT_VMCNT0);
     __syncthreads();
 
-    for (int jt = 0; jt <= qt; ++jt) {
-        const int cur = jt & 1;
-        if (jt < qt)
-            copy_tiles(cur ^ 1, jt + 1);
+    auto tile_step = [&](int jt, auto parity) {
+        constexpr int PAR = decltype(parity)::value;
+        h8 *const Kcur = PAR ? Ks1 : Ks0, *const Vcur = PAR ? Vs1 : Vs0;
+        if (jt < last_tile)
+            load_tiles(PAR ? Ks0 : Ks1, jt + 1);
 
-        // scores of 64 positions against the wavefront's 16 query rows, transposed
-        f4 st[4];
+        // a wavefront whose every query row lies before the tile has nothing to add (uniform per wavefront)
+        if (jt * PT <= q0 + 16 * QB - 1) {
+            // scores of 64 positions against the wavefront's query rows, transposed: S^T = K . Q'^T
+            f4 st[QB][4];
 #pragma unroll
-        for (int b = 0; b < 4; ++b) {
-            st[b] = f4{0.f, 0.f, 0.f, 0.f};
+            for (int b = 0; b < 4; ++b) {
 #pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                const int row = 16 * b + col, ch = 4 * s + g;
-                st[b] = mfma16x16x32(Ks[cur][row * 16 + (ch ^ (row & 15))], qb[s], st[b]);
+                for (int qi = 0; qi < QB; ++qi)
+                    st[qi][b] = f4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int s = 0; s < 4; ++s) {
+                    const h8 ka = Kcur[key_slot(key_row(b, col), 4 * s + g)];
+#pragma unroll
+                    for (int qi = 0; qi < QB; ++qi)
+                        st[qi][b] = mfma16x16x32(ka, qb[qi][s], st[qi][b]);
+                }
+            }
+            // lane: query row q0 + 16qi + col; st[qi][b][v] belongs to position jt*64 + key_row(b, 4g + v).
+            // Scores are kept in units of log2(e) / sqrt(128), so that the exponentials are bare exp2; only
+            // tiles that reach the diagonal need the mask (it also hides the positions past T).
+            constexpr float kScale = 0.08838834764831845f * 1.4426950408889634f;
+            const bool diagonal = jt * PT + PT - 1 > q0; // uniform per wavefront
+            h8 pb[QB][2];
+#pragma unroll
+            for (int qi = 0; qi < QB; ++qi) {
+                float tmax = -INFINITY;
+                if (diagonal) {
+#pragma unroll
+                    for (int b = 0; b < 4; ++b)
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) {
+                            const int kv = jt * PT + key_row(b, 4 * g + v);
+                            st[qi][b][v] = kv <= q0 + 16 * qi + col ? st[qi][b][v] * kScale : -INFINITY;
+                            tmax = fmaxf(tmax, st[qi][b][v]);
+                        }
+                } else {
+#pragma unroll
+                    for (int b = 0; b < 4; ++b)
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) {
+                            st[qi][b][v] *= kScale;
+                            tmax = fmaxf(tmax, st[qi][b][v]);
+                        }
+                }
+                tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
+                tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+                // the maximum so far; a row the tile does not reach at all keeps its old one (and gets zeros)
+                const float mnew = fmaxf(mx[qi], tmax);
+                const float mref = mnew == -INFINITY ? 0.f : mnew;
+                float psum = 0.f;
+#pragma unroll
+                for (int b = 0; b < 4; ++b)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const float e = __builtin_amdgcn_exp2f(st[qi][b][v] - mref);
+                        psum += e;
+                        pb[qi][b >> 1][4 * (b & 1) + v] = (_Float16)e;
+                    }
+                if (__builtin_amdgcn_ballot_w64(mnew != mx[qi]) != 0) { // some row's maximum moved: rescale
+                    const float alpha = __builtin_amdgcn_exp2f(mx[qi] - mref); // exp2(-inf) = 0 at the start
+                    mx[qi] = mnew;
+                    l[qi] *= alpha;
+#pragma unroll
+                    for (int i = 0; i < 8; ++i)
+                        acc[qi][i] *= alpha;
+                }
+                l[qi] += psum;
+            }
+            // O^T += V^T . P^T; k-slot e of k-step ks is position 32ks + 8g + e: one slot of a value row
+#pragma unroll
+            for (int db = 0; db < 8; ++db) {
+                const int d = 16 * db + col, sw = (d >> 1) & 7;
+#pragma unroll
+                for (int ks = 0; ks < 2; ++ks) {
+                    const h8 va = Vcur[d * 8 + ((4 * ks + g) ^ sw)];
+#pragma unroll
+                    for (int qi = 0; qi < QB; ++qi)
+                        acc[qi][db] = mfma16x16x32(va, pb[qi][ks], acc[qi][db]);
+                }
             }
         }
-        // lane: query row q0 + col, positions jt*64 + 16b + 4g + v
-        float tmax = -INFINITY;
-#pragma unroll
-        for (int b = 0; b < 4; ++b)
-#pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const int kv = jt * PT + 16 * b + 4 * g + v;
-                const float sc = st[b][v] * 0.08838834764831845f; // 1 / sqrt(128)
-                st[b][v] = kv <= q0 + col ? sc : -INFINITY;      // causal mask (also hides positions past T)
-                tmax = fmaxf(tmax, st[b][v]);
-            }
-        tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
-        tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
-        const float mnew = fmaxf(mx, tmax); // finite from the first tile on: position 0 is visible to every row
-        const float alpha = __expf(mx - mnew);
-        mx = mnew;
-        h8 pb[2];
-        float psum = 0.f;
-#pragma unroll
-        for (int b = 0; b < 4; ++b)
-#pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const float e = __expf(st[b][v] - mnew);
-                psum += e;
-                pb[b >> 1][4 * (b & 1) + v] = (_Float16)e;
-            }
-        l = l * alpha + psum;
-#pragma unroll
-        for (int i = 0; i < 8; ++i)
-            acc[i] *= alpha;
-        // O^T += V^T . P^T; k-slot e of k-step ks is position 32ks + 4g + e (e < 4) or 32ks + 16 + 4g + e - 4
-#pragma unroll
-        for (int db = 0; db < 8; ++db) {
-            const int d = 16 * db + col, sw = (d >> 1) & 7;
-            const uint2 *rowp = reinterpret_cast<const uint2 *>(&Vs[cur][d * 8]);
-#pragma unroll
-            for (int ks = 0; ks < 2; ++ks) {
-                const int s0 = 4 * ks + (g >> 1), s1 = s0 + 2;
-                const uint2 lo = rowp[2 * (s0 ^ sw) + (g & 1)], hi = rowp[2 * (s1 ^ sw) + (g & 1)];
-                const u4v both = {lo.x, lo.y, hi.x, hi.y};
-                acc[db] = mfma16x16x32(__builtin_bit_cast(h8, both), pb[ks], acc[db]);
-            }
-        }
+        if (jt < last_tile)
+            store_values(PAR ? Vs0 : Vs1); // last read in the previous step, before its barrier
         __builtin_amdgcn_s_waitcnt(FQ_WAIT_VMCNT0);
         __syncthreads();
+    };
+    int jt = 0;
+    for (; jt + 1 <= last_tile; jt += 2) {
+        tile_step(jt, std::integral_constant<int, 0>{});
+        tile_step(jt + 1, std::integral_constant<int, 1>{});
     }
+    if (jt <= last_tile)
+        tile_step(jt, std::integral_constant<int, 0>{});
 
-    l += __shfl_xor(l, 16, 64);
-    l += __shfl_xor(l, 32, 64);
-    const int q = q0 + col;
-    if (q < p.T) {
-        const float inv = 1.0f / l;
 #pragma unroll
-        for (int db = 0; db < 8; ++db) {
-            const h4 o = {(_Float16)(acc[db][0] * inv), (_Float16)(acc[db][1] * inv), (_Float16)(acc[db][2] * inv),
-                          (_Float16)(acc[db][3] * inv)};
-            *reinterpret_cast<h4 *>(p.out + (size_t)q * p.H + (size_t)head * AD + 16 * db + 4 * g) = o;
+    for (int qi = 0; qi < QB; ++qi) {
+        float lsum = l[qi];
+        lsum += __shfl_xor(lsum, 16, 64);
+        lsum += __shfl_xor(lsum, 32, 64);
+        const int q = q0 + 16 * qi + col;
+        if (q < p.T) {
+            const float inv = 1.0f / lsum;
+#pragma unroll
+            for (int db = 0; db < 8; ++db) {
+                const h4 o = {(_Float16)(acc[qi][db][0] * inv), (_Float16)(acc[qi][db][1] * inv),
+                              (_Float16)(acc[qi][db][2] * inv), (_Float16)(acc[qi][db][3] * inv)};
+                *reinterpret_cast<h4 *>(p.out + (size_t)q * p.H + (size_t)head * AD + 16 * db + 4 * g) = o;
+            }
         }
     }
 }
@@ -450,11 +536,12 @@ int fq_launch_attn_prefill(const void *q, const void *k, const void *v, int T, v
     a.Tp = prefill_tp(T);
     a.Tmax = Tmax;
     a.H = n_heads * AD;
-    const int tiles = a.Tp / PT;
-    hipLaunchKernelGGL(attn_prep_kernel, dim3(tiles, n_heads), dim3(256), 0, st, a);
+    hipLaunchKernelGGL(attn_prep_kernel, dim3(a.Tp / PT, n_heads), dim3(256), 0, st, a);
     int rc = (int)hipGetLastError();
     if (rc != 0)
         return rc;
-    hipLaunchKernelGGL(attn_prefill_kernel, dim3(tiles, n_heads), dim3(256), 0, st, a);
+    a.NQ = (T + QT - 1) / QT;
+    a.heads = n_heads;
+    hipLaunchKernelGGL(attn_prefill_kernel, dim3(a.NQ * n_heads), dim3(256), 0, st, a);
     return (int)hipGetLastError();
 }
