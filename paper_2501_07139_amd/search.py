@@ -134,28 +134,42 @@ class CalibrationEval:
     exp(mean token NLL).  Keeps the input of every block with the node so that a successor restarts at the
     block it changes."""
 
-    def __init__(self, stack, head, x, labels):
+    def __init__(self, stack, head, x, labels, real_blocks: bool = False):
+        """real_blocks: run the blocks as real decoder blocks (rotary embedding, causal attention) with the
+        calibration rows as ONE sequence at positions 0..M-1, instead of the attention-free stack."""
         import torch
 
-        from . import Stack, fq_head_nll_workspace_bytes, fq_stack_workspace_bytes
+        from . import (Stack, fq_head_nll_workspace_bytes, fq_prefill_workspace_bytes, fq_stack_workspace_bytes,
+                       rope_table)
 
         self.stack, self.head, self.x, self.labels = stack, head, x, labels
         self.L = stack.L
         self.one = [Stack([stack.layers[l]]) for l in range(self.L)]
         M = x.shape[0]
-        self.ws = torch.empty(fq_stack_workspace_bytes(M, stack.hidden, stack.ffn), dtype=torch.uint8, device=x.device)
+        self.real = real_blocks
+        if real_blocks:
+            self.ws = torch.empty(fq_prefill_workspace_bytes(M, stack.hidden, stack.ffn), dtype=torch.uint8, device=x.device)
+            self.rope = rope_table(M, device=x.device)
+            self.kc = torch.empty((1, stack.hidden // 128, M, 128), dtype=torch.float16, device=x.device)
+            self.vc = torch.empty_like(self.kc)
+        else:
+            self.ws = torch.empty(fq_stack_workspace_bytes(M, stack.hidden, stack.ffn), dtype=torch.uint8, device=x.device)
         self.ws_head = torch.empty(fq_head_nll_workspace_bytes(M, head.shape[0]), dtype=torch.uint8, device=x.device)
         self.evaluations = 0
         self.blocks_run = 0
 
     def __call__(self, bitvec: BitVec, parent: Optional[Node], entry: Optional[int]):
-        from . import fq_head_nll, fq_stack_forward
+        from . import fq_head_nll, fq_prefill_forward, fq_stack_forward
 
         bv = np.asarray(bitvec, dtype=np.uint8)
         first = 0 if parent is None or parent.state is None else entry // 7
         inputs = [self.x] if first == 0 else list(parent.state[:first + 1])
         for l in range(first, self.L):
-            inputs.append(fq_stack_forward(self.one[l], bv[7 * l:7 * l + 7], inputs[l], workspace=self.ws))
+            if self.real:  # the caches are scratch here: every block of a sequence forward fills its own
+                inputs.append(fq_prefill_forward(self.one[l], bv[7 * l:7 * l + 7], inputs[l], self.kc, self.vc,
+                                                 self.rope, workspace=self.ws))
+            else:
+                inputs.append(fq_stack_forward(self.one[l], bv[7 * l:7 * l + 7], inputs[l], workspace=self.ws))
         nll = fq_head_nll(inputs[self.L], self.head, self.labels, workspace=self.ws_head)
         nll = nll.cpu().numpy().astype(np.float64)
         self.evaluations += 1

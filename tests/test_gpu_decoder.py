@@ -269,3 +269,30 @@ def test_glue_silu_mul_without_norm(fq, torch):
     got = host16(fq.fq_glue(5, dev(torch, g), dev(torch, p)))
     want = oracle.round_f16(oracle.silu_mul(g, p))
     assert ulps(got, want).max() <= 1 and np.mean(got.view(np.uint16) == want.view(np.uint16)) > 0.98
+
+
+def test_calibration_eval_on_real_blocks_matches_the_oracle_perplexity(fq, torch):
+    """calibrationEval of Algorithm 1 with the blocks run as real decoder blocks: perplexity of a hybrid model
+    over one calibration sequence, restarted from a changed block, against the oracle's chain."""
+    from paper_2501_07139_amd import search
+
+    stack, host, sh = build_real_stack(fq, 850, levels=(2, 4, 8))
+    L, H, nh, M, V = sh["layers"], sh["hidden"], sh["hidden"] // 128, 96, 1000
+    x = fq_synth.activations(851, M, H)
+    head = fq_synth.weights(852, V, H, 0.05).astype(np.float16)
+    labels = fq_synth.labels(853, M, V)
+    ev = search.CalibrationEval(stack, dev(torch, head), dev(torch, x), torch.from_numpy(labels).cuda(), real_blocks=True)
+
+    def oracle_ppl(bits):
+        mats = [[host[l][j][bits[7 * l + j]] for j in range(7)] for l in range(L)]
+        logits = oracle.round_f16(oracle.dense_f16(ref.sequence_stack(x, mats, nh), head))
+        return oracle.perplexity(oracle.token_nll(logits, labels))
+
+    up = (8,) * (7 * L)
+    ppl_up, state = ev(up, None, None)
+    assert abs(ppl_up / oracle_ppl(up) - 1) <= 2e-3
+    parent = search.Node(up, ppl_up, None, state)
+    child = up[:9] + (2,) + up[10:]              # block 1, matrix 2 lowered: restart at block 1
+    ppl_c, _ = ev(child, parent, 9)
+    assert ev.blocks_run == L + (L - 1)
+    assert abs(ppl_c / oracle_ppl(child) - 1) <= 2e-3
