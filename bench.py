@@ -306,6 +306,33 @@ def main():
     ms_dec_hosted = timed(lambda: hosted.forward(x_dec), reps)
     del hosted, store
 
+    # beyond the step: the decode kernel on a 70B-shaped matrix (8192 -> 28672), where the fixed cost of a launch
+    # no longer dominates: packed bytes are random, scales and zeros constants (no quantizer run), 4 cold copies
+    big = []
+    BN, BK = 28672, 8192
+    for bb in (2, 4, 8):
+        nb, nm = fq.fq_packed_bytes(BN, BK, bb), fq.fq_meta_count(BN, BK)
+        ws_big = [fq.PackedMatrix(torch.randint(0, 255, (nb,), dtype=torch.uint8, device=dev),
+                                  torch.full((nm,), 0.01, dtype=torch.float16, device=dev),
+                                  torch.full((nm,), 1.0, dtype=torch.float16, device=dev), BN, BK, bb) for _ in range(4)]
+        xb = torch.empty((1, BK), dtype=torch.float16, device=dev).normal_()
+        ob = torch.empty((1, BN), dtype=torch.float16, device=dev)
+
+        def rot_big():
+            for w in ws_big:
+                fq.fq_qlinear(xb, w, out=ob)
+
+        rot_big()
+        torch.cuda.synchronize()
+        gb = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(gb):
+            rot_big()
+        msb = timed(gb.replay, reps) / 4
+        big.append({"N": BN, "K": BK, "bits": bb, "MB": round(ws_big[0].nbytes / 1e6, 1), "us": round(msb * 1e3, 2),
+                    "GBps": round(ws_big[0].nbytes / msb / 1e6, 1),
+                    "frac_hbm_peak": round(ws_big[0].nbytes / msb / 1e6 / PEAK_HBM_GBPS, 4)})
+        del ws_big, gb
+
     traffic = None
     if GEMM_TRAFFIC["kernel_digest"] == kernel_digest() and GEMM_TRAFFIC["fetch_bytes"]:
         traffic = {"fetch_bytes": GEMM_TRAFFIC["fetch_bytes"], "write_bytes": GEMM_TRAFFIC["write_bytes"]}
@@ -352,6 +379,7 @@ def main():
                                             "ms_per_swap": round(swap_s * 1e3, 3), "MB_loaded_per_swap": round(swap_bytes / 1e6, 2),
                                             "GBps_host_to_device": round(swap_bytes / swap_s / 1e9, 1),
                                             "ms_block_decode_of_hosted_model": round(ms_dec_hosted, 4)},
+            "gemv_large_outside_the_step": big,
             "gemv_m1": {"GBps_single_launches": round(block_bytes / gemv_ms_total / 1e6, 1),
                         "GBps_stack_decode": round(gemv_bytes / ms_dec / 1e6, 1),
                         "ms_stack_decode": round(ms_dec, 4), "layers": DECODE_LAYERS,
