@@ -296,3 +296,42 @@ def test_calibration_eval_on_real_blocks_matches_the_oracle_perplexity(fq, torch
     ppl_c, _ = ev(child, parent, 9)
     assert ev.blocks_run == L + (L - 1)
     assert abs(ppl_c / oracle_ppl(child) - 1) <= 2e-3
+
+
+def test_decode_step_and_prefill_replay_from_captured_graphs(fq, torch):
+    """The launches of a decode step and of a prefill forward can be captured and replayed (the library queues
+    kernels only: no memsets, no allocations): every replay, with eager work in between, reproduces the eager
+    result bit for bit."""
+    stack, host, sh = build_real_stack(fq, 860, levels=(3, 8))
+    L, H, nh, Tmax, T = sh["layers"], sh["hidden"], sh["hidden"] // 128, 200, 140
+    bitvec = np.tile(np.array([3, 8, 3, 8, 3, 8, 3], dtype=np.uint8), L)
+    rope = fq.rope_table(Tmax)
+    X = dev(torch, fq_synth.activations(861, T + 1, H))
+    kc = torch.zeros((L, nh, Tmax, 128), dtype=torch.float16, device="cuda")
+    vc = torch.zeros_like(kc)
+    ws_p = torch.empty(fq.fq_prefill_workspace_bytes(T, H, sh["ffn"]), dtype=torch.uint8, device="cuda")
+    ws_d = torch.empty(fq.fq_decode_workspace_bytes(H, sh["ffn"], Tmax), dtype=torch.uint8, device="cuda")
+    out_p = torch.empty((T, H), dtype=torch.float16, device="cuda")
+    out_d = torch.empty(H, dtype=torch.float16, device="cuda")
+    xs, xt = X[:T].contiguous(), X[T].contiguous()
+    fq.fq_prefill_forward(stack, bitvec, xs, kc, vc, rope, out=out_p, workspace=ws_p)   # eager, also the warm-up
+    fq.fq_decode_step(stack, bitvec, xt, kc, vc, T, rope, out=out_d, workspace=ws_d)
+    torch.cuda.synchronize()
+    want_p, want_d, want_k = out_p.clone(), out_d.clone(), kc.clone()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        fq.fq_prefill_forward(stack, bitvec, xs, kc, vc, rope, out=out_p, workspace=ws_p)
+        fq.fq_decode_step(stack, bitvec, xt, kc, vc, T, rope, out=out_d, workspace=ws_d)
+    for r in range(3):
+        out_p.fill_(float("nan"))
+        out_d.fill_(float("nan"))
+        kc.zero_()
+        vc.zero_()
+        ws_p.random_(0, 255)
+        ws_d.random_(0, 255)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out_p.view(torch.int16), want_p.view(torch.int16)), r
+        assert torch.equal(out_d.view(torch.int16), want_d.view(torch.int16)), r
+        assert torch.equal(kc.view(torch.int16), want_k.view(torch.int16)), r
