@@ -31,6 +31,8 @@
 #include "fq_device.h"
 #include "fq_internal.h"
 
+#include <mutex>
+
 namespace {
 
 // ------------------------------------------------------------------ generic
@@ -734,44 +736,54 @@ size_t gemv_stream_lds(int M, int K, int bits, int inputs)
 
 int rows_per_supertile(int bits) { return bits == 2 ? 32 : (bits == 3 ? 64 : 16); }
 
-// Resident workgroups of a streaming kernel on the device for a request of dynamic LDS.
+// Resident workgroups of a streaming kernel on the current device for a request of dynamic LDS.  What is
+// learnt (the CU count, that a kernel's LDS limit has been raised, the last few answers) is kept per device
+// and guarded, so that callers on several threads or devices do not trip over each other.
 int gemv_resident_blocks(GemvKernel kernel, int slot, size_t lds, int *out)
 {
-    static int cus = 0;
-    static bool prepared[14];
-    if (cus == 0) {
-        int dev = 0, n = 0;
-        hipError_t e = hipGetDevice(&dev);
-        if (e != hipSuccess)
-            return (int)e;
+    struct PerDevice {
+        int cus = 0;
+        bool prepared[14] = {};
+        size_t seen_lds[14][4] = {};
+        int seen_blocks[14][4] = {}, seen[14] = {};
+    };
+    static PerDevice table[16];
+    static std::mutex guard;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess)
+        return (int)e;
+    if (dev < 0 || dev >= 16)
+        return (int)hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(guard);
+    PerDevice &d = table[dev];
+    if (d.cus == 0) {
+        int n = 0;
         e = hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev);
         if (e != hipSuccess)
             return (int)e;
-        cus = n;
+        d.cus = n;
     }
-    if (!prepared[slot]) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)GEMV_MAX_LDS);
+    if (!d.prepared[slot]) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)GEMV_MAX_LDS);
         if (e != hipSuccess)
             return (int)e;
-        prepared[slot] = true;
+        d.prepared[slot] = true;
     }
-    // the answer depends only on the kernel and the LDS request: remember the last few
-    static size_t seen_lds[14][4];
-    static int seen_blocks[14][4], seen[14];
-    for (int i = 0; i < seen[slot]; ++i)
-        if (seen_lds[slot][i] == lds) {
-            *out = seen_blocks[slot][i];
+    for (int i = 0; i < d.seen[slot]; ++i)
+        if (d.seen_lds[slot][i] == lds) {
+            *out = d.seen_blocks[slot][i];
             return 0;
         }
     int per_cu = 0;
-    const hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, 64 * GNW, lds);
+    e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, 64 * GNW, lds);
     if (e != hipSuccess)
         return (int)e;
-    *out = cus * (per_cu > 0 ? per_cu : 1);
-    if (seen[slot] < 4) {
-        seen_lds[slot][seen[slot]] = lds;
-        seen_blocks[slot][seen[slot]++] = *out;
+    *out = d.cus * (per_cu > 0 ? per_cu : 1);
+    if (d.seen[slot] < 4) {
+        d.seen_lds[slot][d.seen[slot]] = lds;
+        d.seen_blocks[slot][d.seen[slot]++] = *out;
     }
     return 0;
 }
