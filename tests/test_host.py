@@ -157,3 +157,13 @@ def test_stack_forward_rejects_a_missing_packing_before_launching():
     bitvec[3] = 4
     rc = fq._lib.fq_stack_forward(table, 1, bitvec.ctypes.data_as(ctypes.c_void_p), 4096, 4, 4096, 4096, 16, None)
     assert rc == -6
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py measures one GPU only: asked for more it says so and exits without touching a device."""
+    import subprocess
+    import sys
+
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0 and "one GPU" in (r.stdout + r.stderr)
