@@ -247,91 +247,122 @@ def main():
         gemv_kernels.append({"matrix": fq_synth.MATRIX_NAMES[j], "N": N, "K": K, "bits": int(bitvec[j]),
                              "us": round(ms * 1e3, 2), "GBps": round(nbytes / ms / 1e6, 1)})
 
-    # beyond the step: the same 8 block copies as real decoder blocks (attention over a key/value cache of
-    # 2048 positions), one token at the last position
+    # ---------------------------------------------------------- legs beyond the step
+    # Each runs on its own and reports {"error": ...} if it fails: the step's figures above do not depend on them.
+    def optional(fn):
+        try:
+            return fn()
+        except Exception as e:  # noqa: BLE001 - the reason is reported in the JSON line
+            torch.cuda.synchronize()
+            return {"error": "%s: %s" % (type(e).__name__, e)}
+
     T_CTX = 2048
-    rope = fq.rope_table(T_CTX)
-    kc = torch.empty((DECODE_LAYERS, HIDDEN // 128, T_CTX, 128), dtype=torch.float16, device=dev).normal_()
-    vc = torch.empty_like(kc).normal_()
-    ws_real = torch.empty(fq.fq_decode_workspace_bytes(HIDDEN, FFN, T_CTX), dtype=torch.uint8, device=dev)
-    x_tok = x_dec.view(-1)
-    y_tok = torch.empty_like(x_tok)
-    ms_real = timed(lambda: fq.fq_decode_step(stack_dec, bitvec_dec, x_tok, kc, vc, T_CTX - 1, rope, out=y_tok,
-                                              workspace=ws_real), reps)
-    q1 = torch.empty(HIDDEN, dtype=torch.float16, device=dev).normal_()
-    a1 = torch.empty_like(q1)
 
-    def attn_rot():  # one call per layer's cache: cold reads
-        for l in range(DECODE_LAYERS):
-            fq.fq_attn_decode(q1, q1, q1, kc[l], vc[l], T_CTX - 1, rope, out=a1, workspace=ws_real)
+    def leg_real_blocks():
+        """The 8 block copies as real decoder blocks: one token over a key/value cache of 2048 positions, and
+        the block over a whole sequence of 2048 positions (causal attention)."""
+        rope = fq.rope_table(T_CTX)
+        kc = torch.empty((DECODE_LAYERS, HIDDEN // 128, T_CTX, 128), dtype=torch.float16, device=dev).normal_()
+        vc = torch.empty_like(kc).normal_()
+        ws_real = torch.empty(fq.fq_decode_workspace_bytes(HIDDEN, FFN, T_CTX), dtype=torch.uint8, device=dev)
+        x_tok = x_dec.view(-1)
+        y_tok = torch.empty_like(x_tok)
+        ms_real = timed(lambda: fq.fq_decode_step(stack_dec, bitvec_dec, x_tok, kc, vc, T_CTX - 1, rope, out=y_tok,
+                                                  workspace=ws_real), reps)
+        q1 = torch.empty(HIDDEN, dtype=torch.float16, device=dev).normal_()
+        a1 = torch.empty_like(q1)
 
-    attn_rot()
-    torch.cuda.synchronize()
-    attn_graph = torch.cuda.CUDAGraph()  # replayed from a graph: issued from Python the calls are host-bound
-    with torch.cuda.graph(attn_graph):
+        def attn_rot():  # one call per layer's cache: cold reads
+            for l in range(DECODE_LAYERS):
+                fq.fq_attn_decode(q1, q1, q1, kc[l], vc[l], T_CTX - 1, rope, out=a1, workspace=ws_real)
+
         attn_rot()
-    ms_attn = timed(attn_graph.replay, reps) / DECODE_LAYERS
-    kv_bytes = 2.0 * T_CTX * HIDDEN * 2
-    # ... and the block over a whole sequence of 2048 positions as a real block (causal attention)
-    ws_pre = torch.empty(fq.fq_prefill_workspace_bytes(M_FWD, HIDDEN, FFN), dtype=torch.uint8, device=dev)
-    ms_prefill = timed(lambda: fq.fq_prefill_forward(stack_fwd, bitvec, x_fwd, kc[:1], vc[:1], rope, out=h_out,
-                                                     workspace=ws_pre), reps)
-    qkv_rows = [torch.empty((M_FWD, HIDDEN), dtype=torch.float16, device=dev).normal_() for _ in range(3)]
-    a_rows = torch.empty_like(qkv_rows[0])
-    ms_attn_pre = timed(lambda: fq.fq_attn_prefill(qkv_rows[0], qkv_rows[1], qkv_rows[2], kc[0], vc[0], rope, out=a_rows,
-                                                   workspace=ws_pre), reps)
-    attn_flops = 2 * 2.0 * (HIDDEN // 128) * 128 * (M_FWD * (M_FWD + 1) / 2)  # causal: QK^T and PV
-    del kc, vc, ws_pre
-
-    # beyond the step: a run-time transition, one matrix swapped for its other stored width and back.  The new
-    # packing comes from pinned host memory, so this is a PCIe figure.
-    from paper_2501_07139_amd import elastic
-
-    store = elastic.HostStore([[{int(bitvec[j]): host_q[j], **({swap_bits: swap_q} if j == SWAP_ENTRY else {})}
-                                for j in range(7)]])
-    members = [tuple(int(b) for b in bitvec), tuple(swap_bits if j == SWAP_ENTRY else int(b) for j, b in enumerate(bitvec))]
-    members.sort(key=lambda v: -v[SWAP_ENTRY])
-    hosted = elastic.ElasticModel(store, members)
-    for _ in range(2):  # first use: allocations
-        hosted.move_to(1)
-        hosted.move_to(0)
-    torch.cuda.synchronize()
-    loaded0, t0 = hosted.bytes_loaded, time.perf_counter()
-    for _ in range(5):
-        hosted.move_to(1)
-        hosted.move_to(0)
-    torch.cuda.synchronize()
-    swap_s = (time.perf_counter() - t0) / 10
-    swap_bytes = (hosted.bytes_loaded - loaded0) / 10
-    ms_dec_hosted = timed(lambda: hosted.forward(x_dec), reps)
-    del hosted, store
-
-    # beyond the step: the decode kernel on a 70B-shaped matrix (8192 -> 28672), where the fixed cost of a launch
-    # no longer dominates: packed bytes are random, scales and zeros constants (no quantizer run), 4 cold copies
-    big = []
-    BN, BK = 28672, 8192
-    for bb in (2, 4, 8):
-        nb, nm = fq.fq_packed_bytes(BN, BK, bb), fq.fq_meta_count(BN, BK)
-        ws_big = [fq.PackedMatrix(torch.randint(0, 255, (nb,), dtype=torch.uint8, device=dev),
-                                  torch.full((nm,), 0.01, dtype=torch.float16, device=dev),
-                                  torch.full((nm,), 1.0, dtype=torch.float16, device=dev), BN, BK, bb) for _ in range(4)]
-        xb = torch.empty((1, BK), dtype=torch.float16, device=dev).normal_()
-        ob = torch.empty((1, BN), dtype=torch.float16, device=dev)
-
-        def rot_big():
-            for w in ws_big:
-                fq.fq_qlinear(xb, w, out=ob)
-
-        rot_big()
         torch.cuda.synchronize()
-        gb = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(gb):
+        attn_graph = torch.cuda.CUDAGraph()  # replayed from a graph: issued from Python the calls are host-bound
+        with torch.cuda.graph(attn_graph):
+            attn_rot()
+        ms_attn = timed(attn_graph.replay, reps) / DECODE_LAYERS
+        kv_bytes = 2.0 * T_CTX * HIDDEN * 2
+        ws_pre = torch.empty(fq.fq_prefill_workspace_bytes(M_FWD, HIDDEN, FFN), dtype=torch.uint8, device=dev)
+        pre_out = torch.empty_like(x_fwd)
+        ms_prefill = timed(lambda: fq.fq_prefill_forward(stack_fwd, bitvec, x_fwd, kc[:1], vc[:1], rope, out=pre_out,
+                                                         workspace=ws_pre), reps)
+        qkv_rows = [torch.empty((M_FWD, HIDDEN), dtype=torch.float16, device=dev).normal_() for _ in range(3)]
+        a_rows = torch.empty_like(qkv_rows[0])
+        ms_attn_pre = timed(lambda: fq.fq_attn_prefill(qkv_rows[0], qkv_rows[1], qkv_rows[2], kc[0], vc[0], rope,
+                                                       out=a_rows, workspace=ws_pre), reps)
+        attn_flops = 2 * 2.0 * (HIDDEN // 128) * 128 * (M_FWD * (M_FWD + 1) / 2)  # causal: QK^T and PV
+        return {"decode": {"context": T_CTX, "layers": DECODE_LAYERS, "ms": round(ms_real, 4),
+                           "us_per_block": round(ms_real * 1e3 / DECODE_LAYERS, 2),
+                           "GBps_weights_and_cache": round((gemv_bytes + DECODE_LAYERS * kv_bytes) / ms_real / 1e6, 1),
+                           "attention_us": round(ms_attn * 1e3, 2),
+                           "attention_GBps": round(kv_bytes / ms_attn / 1e6, 1),
+                           "attention_frac_hbm_peak": round(kv_bytes / ms_attn / 1e6 / PEAK_HBM_GBPS, 4)},
+                "prefill": {"positions": M_FWD, "ms_block": round(ms_prefill, 4),
+                            "tflops_block": round((gemm_flops + attn_flops) / ms_prefill / 1e9, 1),
+                            "attention_ms": round(ms_attn_pre, 4),
+                            "attention_tflops": round(attn_flops / ms_attn_pre / 1e9, 1)}}
+
+    def leg_transition():
+        """A run-time transition: one matrix swapped for its other stored width and back.  The new packing comes
+        from pinned host memory, so this is a PCIe figure."""
+        from paper_2501_07139_amd import elastic
+
+        store = elastic.HostStore([[{int(bitvec[j]): host_q[j], **({swap_bits: swap_q} if j == SWAP_ENTRY else {})}
+                                    for j in range(7)]])
+        members = [tuple(int(b) for b in bitvec),
+                   tuple(swap_bits if j == SWAP_ENTRY else int(b) for j, b in enumerate(bitvec))]
+        members.sort(key=lambda v: -v[SWAP_ENTRY])
+        hosted = elastic.ElasticModel(store, members)
+        for _ in range(2):  # first use: allocations
+            hosted.move_to(1)
+            hosted.move_to(0)
+        torch.cuda.synchronize()
+        loaded0, t0 = hosted.bytes_loaded, time.perf_counter()
+        for _ in range(5):
+            hosted.move_to(1)
+            hosted.move_to(0)
+        torch.cuda.synchronize()
+        swap_s = (time.perf_counter() - t0) / 10
+        swap_bytes = (hosted.bytes_loaded - loaded0) / 10
+        ms_dec_hosted = timed(lambda: hosted.forward(x_dec), reps)
+        return {"matrix": fq_synth.MATRIX_NAMES[SWAP_ENTRY], "widths": [int(bitvec[SWAP_ENTRY]), swap_bits],
+                "ms_per_swap": round(swap_s * 1e3, 3), "MB_loaded_per_swap": round(swap_bytes / 1e6, 2),
+                "GBps_host_to_device": round(swap_bytes / swap_s / 1e9, 1),
+                "ms_block_decode_of_hosted_model": round(ms_dec_hosted, 4)}
+
+    def leg_gemv_large():
+        """The decode kernel on a 70B-shaped matrix (8192 -> 28672), where the fixed cost of a launch no longer
+        dominates: packed bytes are random, scales and zeros constants (no quantizer run), 4 cold copies."""
+        big = []
+        BN, BK = 28672, 8192
+        for bb in (2, 4, 8):
+            nb, nm = fq.fq_packed_bytes(BN, BK, bb), fq.fq_meta_count(BN, BK)
+            ws_big = [fq.PackedMatrix(torch.randint(0, 255, (nb,), dtype=torch.uint8, device=dev),
+                                      torch.full((nm,), 0.01, dtype=torch.float16, device=dev),
+                                      torch.full((nm,), 1.0, dtype=torch.float16, device=dev), BN, BK, bb) for _ in range(4)]
+            xb = torch.empty((1, BK), dtype=torch.float16, device=dev).normal_()
+            ob = torch.empty((1, BN), dtype=torch.float16, device=dev)
+
+            def rot_big():
+                for w in ws_big:
+                    fq.fq_qlinear(xb, w, out=ob)
+
             rot_big()
-        msb = timed(gb.replay, reps) / 4
-        big.append({"N": BN, "K": BK, "bits": bb, "MB": round(ws_big[0].nbytes / 1e6, 1), "us": round(msb * 1e3, 2),
-                    "GBps": round(ws_big[0].nbytes / msb / 1e6, 1),
-                    "frac_hbm_peak": round(ws_big[0].nbytes / msb / 1e6 / PEAK_HBM_GBPS, 4)})
-        del ws_big, gb
+            torch.cuda.synchronize()
+            gb = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(gb):
+                rot_big()
+            msb = timed(gb.replay, reps) / 4
+            big.append({"N": BN, "K": BK, "bits": bb, "MB": round(ws_big[0].nbytes / 1e6, 1), "us": round(msb * 1e3, 2),
+                        "GBps": round(ws_big[0].nbytes / msb / 1e6, 1),
+                        "frac_hbm_peak": round(ws_big[0].nbytes / msb / 1e6 / PEAK_HBM_GBPS, 4)})
+            del ws_big, gb
+        return big
+
+    real_blocks = optional(leg_real_blocks)
+    transition = optional(leg_transition)
+    gemv_large = optional(leg_gemv_large)
 
     traffic = None
     if GEMM_TRAFFIC["kernel_digest"] == kernel_digest() and GEMM_TRAFFIC["fetch_bytes"]:
@@ -365,21 +396,10 @@ def main():
                                            "max_abs_diff_to_fused": float((nll_two - nll).abs().max().item())},
             "logit_l2_outside_the_step": {"GBps": round(2 * nll_bytes / ms_l2 / 1e6, 1), "ms": round(ms_l2, 4),
                                           "frac_hbm_peak": round(2 * nll_bytes / ms_l2 / 1e6 / PEAK_HBM_GBPS, 4)},
-            "real_decode_outside_the_step": {"context": T_CTX, "layers": DECODE_LAYERS, "ms": round(ms_real, 4),
-                                             "us_per_block": round(ms_real * 1e3 / DECODE_LAYERS, 2),
-                                             "GBps_weights_and_cache": round((gemv_bytes + DECODE_LAYERS * kv_bytes) / ms_real / 1e6, 1),
-                                             "attention_us": round(ms_attn * 1e3, 2),
-                                             "attention_GBps": round(kv_bytes / ms_attn / 1e6, 1),
-                                             "attention_frac_hbm_peak": round(kv_bytes / ms_attn / 1e6 / PEAK_HBM_GBPS, 4)},
-            "real_prefill_outside_the_step": {"positions": M_FWD, "ms_block": round(ms_prefill, 4),
-                                              "tflops_block": round((gemm_flops + attn_flops) / ms_prefill / 1e9, 1),
-                                              "attention_ms": round(ms_attn_pre, 4),
-                                              "attention_tflops": round(attn_flops / ms_attn_pre / 1e9, 1)},
-            "transition_outside_the_step": {"matrix": fq_synth.MATRIX_NAMES[SWAP_ENTRY], "widths": [int(bitvec[SWAP_ENTRY]), swap_bits],
-                                            "ms_per_swap": round(swap_s * 1e3, 3), "MB_loaded_per_swap": round(swap_bytes / 1e6, 2),
-                                            "GBps_host_to_device": round(swap_bytes / swap_s / 1e9, 1),
-                                            "ms_block_decode_of_hosted_model": round(ms_dec_hosted, 4)},
-            "gemv_large_outside_the_step": big,
+            "real_decode_outside_the_step": real_blocks.get("decode", real_blocks),
+            "real_prefill_outside_the_step": real_blocks.get("prefill", real_blocks),
+            "transition_outside_the_step": transition,
+            "gemv_large_outside_the_step": gemv_large,
             "gemv_m1": {"GBps_single_launches": round(block_bytes / gemv_ms_total / 1e6, 1),
                         "GBps_stack_decode": round(gemv_bytes / ms_dec / 1e6, 1),
                         "ms_stack_decode": round(ms_dec, 4), "layers": DECODE_LAYERS,
