@@ -360,7 +360,49 @@ def main():
             del ws_big, gb
         return big
 
+    def leg_full_stack():
+        """The whole 32-block 7B-shaped stack with all four widths of every matrix resident (random packed
+        bytes, constant scales and zeros: no quantizer run), scored for a few seeded bit vectors averaging
+        about 3.5 bits: one calibration sequence of 2048 tokens through the stack, the head and the loss."""
+        L_FULL, CANDS = 32, 6
+        layers = []
+        resident = 0
+        for _ in range(L_FULL):
+            mats = []
+            for (N, K) in shapes:
+                by = {}
+                for bb in (2, 3, 4, 8):
+                    nb, nm = fq.fq_packed_bytes(N, K, bb), fq.fq_meta_count(N, K)
+                    by[bb] = fq.PackedMatrix(torch.randint(0, 255, (nb,), dtype=torch.uint8, device=dev),
+                                             torch.full((nm,), 0.01, dtype=torch.float16, device=dev),
+                                             torch.full((nm,), float((1 << bb) // 2), dtype=torch.float16, device=dev),
+                                             N, K, bb)
+                    resident += by[bb].nbytes
+                mats.append(by)
+            layers.append(mats)
+        full = fq.Stack(layers)
+        vecs = [fq_synth.bit_vector(SEED + 10 + c, 7 * L_FULL, probs=(0.3, 0.3, 0.3, 0.1)) for c in range(CANDS)]
+        hid = torch.empty_like(x_fwd)
+        losses = torch.empty(M_FWD, dtype=torch.float32, device=dev)
+
+        def score(c):
+            fq.fq_stack_forward(full, vecs[c], x_fwd, out=hid, workspace=ws_fwd)
+            fq.fq_head_nll(hid, head, labels, out=losses, workspace=ws_head)
+
+        score(0)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for c in range(CANDS):
+            score(c)
+        torch.cuda.synchronize()
+        per = (time.perf_counter() - t0) / CANDS
+        flops = L_FULL * gemm_flops + head_flops
+        return {"blocks": L_FULL, "resident_GB": round(resident / 1e9, 2), "candidates": CANDS, "tokens": M_FWD,
+                "mean_bits": round(float(np.mean(np.concatenate(vecs))), 2), "ms_per_candidate_sequence": round(per * 1e3, 3),
+                "tflops": round(flops / per / 1e12, 1), "finite": bool(torch.isfinite(losses).all().item())}
+
     real_blocks = optional(leg_real_blocks)
+    full_stack = optional(leg_full_stack)
     transition = optional(leg_transition)
     gemv_large = optional(leg_gemv_large)
 
@@ -398,6 +440,7 @@ def main():
                                           "frac_hbm_peak": round(2 * nll_bytes / ms_l2 / 1e6 / PEAK_HBM_GBPS, 4)},
             "real_decode_outside_the_step": real_blocks.get("decode", real_blocks),
             "real_prefill_outside_the_step": real_blocks.get("prefill", real_blocks),
+            "full_stack_sweep_outside_the_step": full_stack,
             "transition_outside_the_step": transition,
             "gemv_large_outside_the_step": gemv_large,
             "gemv_m1": {"GBps_single_launches": round(block_bytes / gemv_ms_total / 1e6, 1),
