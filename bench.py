@@ -401,7 +401,20 @@ def main():
                 "mean_bits": round(float(np.mean(np.concatenate(vecs))), 2), "ms_per_candidate_sequence": round(per * 1e3, 3),
                 "tflops": round(flops / per / 1e12, 1), "finite": bool(torch.isfinite(losses).all().item())}
 
+    def leg_hbm_reference():
+        """What plain device copies reach on this machine, as context for the HBM-bound figures: bytes read plus bytes
+        written per second, for a small and a large buffer."""
+        out = []
+        for mb in (48, 1024):
+            src = torch.empty(mb << 20, dtype=torch.uint8, device=dev).random_(0, 255)
+            dst = torch.empty_like(src)
+            ms = timed(lambda: dst.copy_(src), reps)
+            out.append({"MB": mb, "us": round(ms * 1e3, 2), "GBps_read_plus_write": round(2.0 * (mb << 20) / ms / 1e6, 1)})
+            del src, dst
+        return out
+
     real_blocks = optional(leg_real_blocks)
+    hbm_reference = optional(leg_hbm_reference)
     full_stack = optional(leg_full_stack)
     transition = optional(leg_transition)
     gemv_large = optional(leg_gemv_large)
@@ -440,6 +453,7 @@ def main():
                                           "frac_hbm_peak": round(2 * nll_bytes / ms_l2 / 1e6 / PEAK_HBM_GBPS, 4)},
             "real_decode_outside_the_step": real_blocks.get("decode", real_blocks),
             "real_prefill_outside_the_step": real_blocks.get("prefill", real_blocks),
+            "device_copy_reference_outside_the_step": hbm_reference,
             "full_stack_sweep_outside_the_step": full_stack,
             "transition_outside_the_step": transition,
             "gemv_large_outside_the_step": gemv_large,
