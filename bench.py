@@ -413,7 +413,42 @@ def main():
             del src, dst
         return out
 
+    def leg_by_width():
+        """Every distinct matrix shape of the block at every stored width (random packed bytes, constant scales
+        and zeros): the dequant-GEMM at M=2048 and the decode kernel at M=1 (graph replay over 8 copies)."""
+        table = []
+        for (N, K) in ((4096, 4096), (11008, 4096), (4096, 11008)):
+            xm = torch.empty((M_FWD, K), dtype=torch.float16, device=dev).normal_()
+            x1 = torch.empty((1, K), dtype=torch.float16, device=dev).normal_()
+            om = torch.empty((M_FWD, N), dtype=torch.float16, device=dev)
+            o1 = torch.empty((1, N), dtype=torch.float16, device=dev)
+            for bb in (2, 3, 4, 8):
+                nb, nm = fq.fq_packed_bytes(N, K, bb), fq.fq_meta_count(N, K)
+                cps = [fq.PackedMatrix(torch.randint(0, 255, (nb,), dtype=torch.uint8, device=dev),
+                                       torch.full((nm,), 0.01, dtype=torch.float16, device=dev),
+                                       torch.full((nm,), float((1 << bb) // 2), dtype=torch.float16, device=dev), N, K, bb)
+                       for _ in range(DECODE_LAYERS)]
+                ms_g = timed(lambda: fq.fq_qlinear(xm, cps[0], out=om), reps)
+
+                def rot1():
+                    for w in cps:
+                        fq.fq_qlinear(x1, w, out=o1)
+
+                rot1()
+                torch.cuda.synchronize()
+                g1 = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g1):
+                    rot1()
+                ms_v = timed(g1.replay, reps) / DECODE_LAYERS
+                nbytes = cps[0].nbytes + 2 * K + 2 * N
+                table.append({"N": N, "K": K, "bits": bb, "gemm_ms": round(ms_g, 4),
+                              "gemm_tflops": round(2.0 * M_FWD * N * K / ms_g / 1e9, 1), "gemv_us": round(ms_v * 1e3, 2),
+                              "gemv_GBps": round(nbytes / ms_v / 1e6, 1)})
+                del cps, g1
+        return table
+
     real_blocks = optional(leg_real_blocks)
+    by_width = optional(leg_by_width)
     hbm_reference = optional(leg_hbm_reference)
     full_stack = optional(leg_full_stack)
     transition = optional(leg_transition)
@@ -454,6 +489,7 @@ def main():
             "real_decode_outside_the_step": real_blocks.get("decode", real_blocks),
             "real_prefill_outside_the_step": real_blocks.get("prefill", real_blocks),
             "device_copy_reference_outside_the_step": hbm_reference,
+            "every_shape_at_every_width_outside_the_step": by_width,
             "full_stack_sweep_outside_the_step": full_stack,
             "transition_outside_the_step": transition,
             "gemv_large_outside_the_step": gemv_large,
