@@ -209,8 +209,8 @@ int fq_head_nll(const void *x, int M, const void *W, int V, int K, const int32_t
                 void *workspace, size_t workspace_bytes, void *stream);
 
 /*
- * Row-wise Euclidean distance between two sets of logits (Section "Search
- * method": the sensitivity value of a module is the Euclidean distance between
+ * Row-wise Euclidean distance between two sets of logits (Section "Efficient
+ * Design Space Navigation": the sensitivity value of a module is the Euclidean distance between
  * the logits of the hybrid model with that module lowered and those of
  * QM(n_up)):  dist[m] = sqrt(sum_v (a[m,v] - b[m,v])^2), differences, squares
  * and the sum in fp32.  a, b fp16 [M,V] row-major: device, read, 16-byte

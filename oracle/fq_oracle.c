@@ -402,7 +402,7 @@ int ora_token_nll(const uint16_t *logits, const int32_t *labels, int M, int V, d
 
 /*
  * Euclidean distance between two sets of fp16 logits, row by row (Section
- * "Search method": the sensitivity value of a module is the Euclidean distance
+ * "Efficient Design Space Navigation": the sensitivity value of a module is the Euclidean distance
  * between the logits of the hybrid model and those of QM(n_up)):
  *   dist[m] = sqrt(sum_v (a[m,v] - b[m,v])^2)
  * The distance over a whole batch of rows is sqrt(sum_m dist[m]^2).

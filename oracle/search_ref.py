@@ -1,11 +1,12 @@
 """Plain reference of the ensemble tree search (FlexQuant, arXiv 2501.07139, Algorithm 1 and the prose of
-Section "Search method").  Test infrastructure: slow, no caching, no GPU; only the tests use it.
+Section "Efficient Design Space Navigation").  Test infrastructure: slow, no caching, no GPU; only the tests use it.
 
 Steps, in the paper's order and names, for a beam of #stem paths (the prose's reading of the single list of
 the listing):
   EQM_last        the last model of every path
-  candidateGenerator   every model obtained from an EQM_last by moving ONE matrix to the next lower stored
-                       bit-width (one-way: never up)
+  candidateGenerator   every model obtained from an EQM_last by moving ONE matrix to one of its lower stored
+                       bit-widths (one-way: never up); below QM(n_up) these are the (m+1) * #module options
+                       the section counts
   analysisFilter  per EQM_last, the #branch candidates whose (matrix, new bits) has the smallest value in the
                   pre-built sensitivity table
   calibrationEval the perplexity of a candidate, from the caller's function
@@ -21,7 +22,8 @@ def footprint(bits, shapes, group=128):
     return sum(n * k * int(b) // 8 + 2 * 2 * n * (k // group) for b, (n, k) in zip(bits, shapes))
 
 
-def tree_search_ref(start, levels, sensitivity, calibration_eval, shapes, stems, branches):
+def tree_search_ref(start, levels, sensitivity, calibration_eval, shapes, stems, branches, pools=None):
+    """pools, if a list, receives the candidates scored by every iteration, in rank order."""
     levels = sorted(levels)
     start = tuple(int(b) for b in start)
     paths = [[(start, calibration_eval(start))]]
@@ -32,13 +34,12 @@ def tree_search_ref(start, levels, sensitivity, calibration_eval, shapes, stems,
             last = path[-1][0]
             cands = []
             for entry in range(len(last)):
-                pos = levels.index(last[entry])
-                if pos == 0:
-                    continue  # already at n_low
-                lower = levels[pos - 1]
-                cand = list(last)
-                cand[entry] = lower
-                cands.append((sensitivity[(entry, lower)], entry, lower, tuple(cand)))
+                for lower in levels:
+                    if lower >= last[entry]:
+                        continue  # one-way: only lower stored widths
+                    cand = list(last)
+                    cand[entry] = lower
+                    cands.append((sensitivity[(entry, lower)], entry, lower, tuple(cand)))
             cands.sort()
             for _, _, _, cand in cands[:branches]:
                 if cand not in seen:
@@ -47,6 +48,8 @@ def tree_search_ref(start, levels, sensitivity, calibration_eval, shapes, stems,
         if not pooled:
             break
         ranked = sorted((calibration_eval(c), footprint(c, shapes), c, pi) for c, pi in pooled)
+        if pools is not None:
+            pools.append([c for _, _, c, _ in ranked])
         paths = [paths[pi] + [(c, ppl)] for ppl, _, c, pi in ranked[:stems]]
     return sorted(paths, key=lambda p: (float(np.mean([ppl for _, ppl in p])), p[-1][0]))
 

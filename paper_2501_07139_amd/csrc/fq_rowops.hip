@@ -200,7 +200,7 @@ int fq_launch_glue(int op, const void *a, const void *b, const void *c, int M, i
 }
 
 // Row-wise Euclidean distance between two logit arrays (sensitivity analysis of the search, Section
-// "Search method").  One workgroup per row, one pass over both rows with 128-bit loads; differences and
+// "Efficient Design Space Navigation").  One workgroup per row, one pass over both rows with 128-bit loads; differences and
 // squares in fp32, four partial sums per thread, then a fixed-order reduction.
 __global__ __launch_bounds__(256) void logit_l2_kernel(const _Float16 *__restrict__ a, const _Float16 *__restrict__ b,
                                                        int V, float *__restrict__ dist)

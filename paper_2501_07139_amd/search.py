@@ -1,16 +1,19 @@
 """Tree search for the ensemble of hybrid models (FlexQuant, arXiv 2501.07139, Algorithm 1), as a driver
 over the library's entry points.
 
-An EQM is a bit vector: one stored bit-width per matrix.  From QM(n_up) the search lowers one matrix by one
-stored level per step (transitions are one-way) until QM(n_low) is reached; every step generates the
-successors of the current models, keeps the #branch least sensitive ones per model (analysis filter, from
+An EQM is a bit vector: one stored bit-width per matrix.  From QM(n_up) the search lowers one matrix per step
+to any of its lower stored bit-widths (transitions are one-way; Section "Efficient Design Space Navigation"
+counts (m+1) * #module options below the root, m the number of models between n_low and n_up) until
+QM(n_low) is reached; every step generates the successors of the current models, keeps the #branch least sensitive ones per model (analysis filter, from
 the pre-built table of `sweep.sensitivity_table`), scores those on the calibration rows (perplexity) and
 keeps the #stem best as the new current models.
 
 Readings of the text (Algorithm 1 keeps one list where the prose keeps #stem of them): the search is a beam
 of #stem paths; the candidates of all current models form one pool, duplicates are scored once, the pool is
 ranked by perplexity (ties: smaller footprint, then the bit vector itself) and its first #stem members
-become the current models, each remembering its parent.  A current model already at QM(n_low) generates
+become the current models, each remembering its parent.  A candidate may coincide with a model another
+path reached earlier (one path lowers a matrix in two steps, another in one): it is scored again and, if
+kept, the two paths continue as separate ensembles.  A current model already at QM(n_low) generates
 nothing; the search ends when the pool is empty.  The output is every surviving path, best first by mean
 perplexity of its members.
 
@@ -35,13 +38,12 @@ def footprint_bytes(bitvec: Sequence[int], shapes: Sequence[Tuple[int, int]], gr
 
 
 def successors(bitvec: BitVec, levels: Sequence[int]) -> List[Tuple[int, int, BitVec]]:
-    """(entry, new bits, new vector) for every entry lowered to the next stored level below its own."""
+    """(entry, new bits, new vector) for every entry lowered to each stored level below its own: from
+    QM(n_up) these are the (m+1) * #module options of Section "Efficient Design Space Navigation"."""
     order = sorted(levels)
     out = []
     for e, b in enumerate(bitvec):
-        i = order.index(b)
-        if i > 0:
-            nb = order[i - 1]
+        for nb in order[:order.index(b)]:
             out.append((e, nb, bitvec[:e] + (nb,) + bitvec[e + 1:]))
     return out
 

@@ -1,6 +1,6 @@
 """Sensitivity analysis of the ensemble search, as a driver over the library's entry points.
 
-FlexQuant (arXiv 2501.07139, Section "Search method") ranks the candidates of every search step with a
+FlexQuant (arXiv 2501.07139, Section "Efficient Design Space Navigation") ranks the candidates of every search step with a
 table built once: take QM(n_up), lower one module at a time to each lower bit-width, and record the
 Euclidean distance between the logits of that hybrid model and those of QM(n_up) on the calibration
 batch.  The smaller the distance, the earlier the module is lowered.

@@ -521,7 +521,7 @@ def test_tree_search_on_the_gpu_makes_choices_the_oracle_agrees_with(fq, torch):
     trace = []
     stems, branches = 2, 3
     paths = search.tree_search(up, levels, table, ev, shapes, stems, branches, trace=trace)
-    assert len(trace) == 7 * L * 2                      # (levels - 1) steps per matrix
+    assert 7 * L <= len(trace) <= 7 * L * 2             # every matrix goes down in one or two steps
     assert ev.blocks_run < ev.evaluations * L           # successors restart at the block they change
     for path in paths:
         assert path[-1].bitvec == (2,) * (7 * L)
