@@ -19,6 +19,8 @@
  *     only accessed by stream-ordered work queued by the call.
  *   - `stream` is a hipStream_t passed as void*; NULL means the default
  *     stream.  Device functions only enqueue work; they do not synchronise.
+ *     The first device call on a device also prepares the library's kernels
+ *     there (see fq_init): call fq_init() before capturing calls into a graph.
  *   - bits is one of 2, 3, 4, 8; group must be 128; K must be a multiple of
  *     128.  fp16 values cross the boundary as IEEE binary16 bit patterns.
  *
@@ -68,6 +70,16 @@ const char *fq_last_error(void);
 /* Library version string.  Host. */
 const char *fq_version(void);
 
+/*
+ * Prepare the library on the current device: raise the LDS limit of the decode
+ * kernels and learn how many of their workgroups the device keeps resident.
+ * Idempotent and thread-safe; once per device.  Every device function does this
+ * by itself on its first call on a device, which is not something a stream
+ * capture may contain: a caller that captures graphs calls fq_init() first,
+ * with the device current.  FQ_ERR_HIP if the runtime refuses.
+ */
+int fq_init(void);
+
 /* ------------------------------------------------------------------ host --- */
 
 /*
@@ -85,14 +97,20 @@ const char *fq_version(void);
 int fq_quantize_rtn(const float *W, int N, int K, int bits, int group,
                     uint8_t *codes, uint16_t *scales, uint16_t *zeros);
 
-/* Bytes of the packed buffer for an [N,K] matrix: 64*ceil(N/64) * K * bits / 8. 0 on bad arguments. */
+/*
+ * Bytes of the packed buffer for an [N,K] matrix: 64*ceil(N/64) * K * bits / 8,
+ * i.e. exactly `bits` bits per weight (the footprint a module of QM(bits) adds to
+ * a hybrid model, Section "EQM Generation Philosophy").  0 on bad arguments.
+ */
 size_t fq_packed_bytes(int N, int K, int bits);
 
 /* Entries of each tiled scale/zero array: 64*ceil(N/64) * K/128.  0 on bad arguments. */
 size_t fq_meta_count(int N, int K, int group);
 
 /*
- * Pack codes and lay scales/zeros out in the device format described above.
+ * Pack codes and lay scales/zeros out in the device format described above: one
+ * stored form per matrix and bit-width, the "parameters of QM(n)" a hybrid model
+ * draws from (Section "EQM Generation Philosophy").
  * codes u8 [N,K] (values < 2^bits, else FQ_ERR_BITS), scales/zeros fp16
  * [N,K/128] row-major: host, read.  packed_out (fq_packed_bytes bytes),
  * scales_out and zeros_out (fq_meta_count entries each): host, written, pad
@@ -105,7 +123,9 @@ int fq_pack_groups(const uint8_t *codes, const uint16_t *scales, const uint16_t 
 /* ---------------------------------------------------------------- device --- */
 
 /*
- * Dequantize a packed matrix to a dense row-major [N,K] array: fp32
+ * The n-bit layer as the numerical approximation of its FP16 counterpart that
+ * Section "FlexQuant Framework" reasons about, written out: dequantize a packed
+ * matrix to a dense row-major [N,K] array: fp32
  * (out_is_fp16 == 0): float(scale) * (float(code) - float(zero)), each step
  * rounded to fp32; or fp16: that value rounded once.  For parity checks.
  * packed, scales, zeros: device, read.  out: device, written.
@@ -171,14 +191,19 @@ int fq_stack_forward(const fq_layer *layers, int L, const uint8_t *bitvec,
 int fq_glue(int op, const void *a, const void *b, const void *c, int M, int H, void *out, void *stream);
 
 /*
- * Unquantized fp16 linear (the vocabulary head): out[m,n] = sum_k x[m,k] W[n,k],
- * fp32 accumulation, fp16 output.  x [M,K], W [N,K], out [M,N] row-major,
- * device.  K must be a multiple of 128; x and W must each stay below 4 GiB
- * (FQ_ERR_SHAPE otherwise).  Two kernels serve it: 128-row tiles, and 256-row
- * tiles with both operands in LDS once those fill the chip; the environment
- * variable FQ_DENSE_TILE=128|256, read at every call, pins one (tests, tuning).
+ * Unquantized fp16 linear: out[m,n] = sum_k x[m,k] W[n,k], fp32 accumulation,
+ * fp16 output.  It is the vocabulary head whose logits calibrationEval
+ * (Algorithm 1) turns into a perplexity and the sensitivity analysis (Section
+ * "Efficient Design Space Navigation") compares; the head is not quantized.
+ * x [M,K], W [N,K], out [M,N] row-major, device.  K must be a multiple of 128;
+ * x and W must each stay below 4 GiB (FQ_ERR_SHAPE otherwise).  Two kernels serve
+ * it: 128-row tiles, and 256-row tiles with both operands in LDS once those fill
+ * the chip.  fq_dense_f16_tile is the same call with the choice made by the
+ * caller: tile_rows = 128 or 256 pins a kernel (any size; for tests and tuning),
+ * 0 leaves it to the library; anything else is FQ_ERR_SHAPE.
  */
 int fq_dense_f16(const void *x, int M, const void *W, int N, int K, void *out, void *stream);
+int fq_dense_f16_tile(const void *x, int M, const void *W, int N, int K, void *out, int tile_rows, void *stream);
 
 /*
  * Fused log-softmax cross-entropy per token (the quantity whose mean,
@@ -256,6 +281,14 @@ int fq_logit_l2(const void *a, const void *b, int M, int V, float *dist_out, voi
  * fq_prefill_workspace_bytes(T, hidden, ffn) bytes.  FQ_ERR_SHAPE unless
  * 0 < T <= Tmax <= 131072.
  */
+/*
+ * fq_rope_table: the (cos, sin) table the calls below take, for positions
+ * 0..Tmax-1: out[t][i] = (cos, sin)(t * base^(-2i/head_dim)), i < head_dim/2,
+ * evaluated in fp64 and rounded once to fp32.  out: host, Tmax*head_dim floats,
+ * written; the caller copies it to the device.  FQ_ERR_SHAPE unless Tmax > 0,
+ * head_dim even and positive, base > 0.
+ */
+int fq_rope_table(int Tmax, int head_dim, double base, float *out);
 size_t fq_attn_workspace_bytes(int Tmax, int n_heads);
 size_t fq_decode_workspace_bytes(int hidden, int ffn, int Tmax);
 int fq_attn_decode(const void *q, const void *k, const void *v, void *k_cache, void *v_cache, int pos, int Tmax,

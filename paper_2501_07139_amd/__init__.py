@@ -61,7 +61,10 @@ def _load() -> ctypes.CDLL:
         "fq_stack_workspace_bytes": (sz, [ci, ci, ci]),
         "fq_stack_forward": (ci, [ctypes.POINTER(fq_layer), ci, vp, vp, ci, vp, vp, sz, vp]),
         "fq_glue": (ci, [ci, vp, vp, vp, ci, ci, vp, vp]),
+        "fq_init": (ci, []),
         "fq_dense_f16": (ci, [vp, ci, vp, ci, ci, vp, vp]),
+        "fq_dense_f16_tile": (ci, [vp, ci, vp, ci, ci, vp, ci, vp]),
+        "fq_rope_table": (ci, [ci, ci, ctypes.c_double, vp]),
         "fq_token_nll": (ci, [vp, vp, ci, ci, vp, vp]),
         "fq_logit_l2": (ci, [vp, vp, ci, ci, vp, vp]),
         "fq_head_nll_workspace_bytes": (sz, [ci, ci]),
@@ -87,7 +90,8 @@ EXPORTS = ("fq_last_error", "fq_version", "fq_quantize_rtn", "fq_packed_bytes", 
            "fq_dequant", "fq_qlinear", "fq_stack_workspace_bytes", "fq_stack_forward", "fq_glue", "fq_dense_f16",
            "fq_token_nll", "fq_logit_l2", "fq_head_nll_workspace_bytes", "fq_head_nll",
            "fq_attn_workspace_bytes", "fq_decode_workspace_bytes", "fq_attn_decode", "fq_decode_step",
-           "fq_attn_prefill_workspace_bytes", "fq_prefill_workspace_bytes", "fq_attn_prefill", "fq_prefill_forward")
+           "fq_attn_prefill_workspace_bytes", "fq_prefill_workspace_bytes", "fq_attn_prefill", "fq_prefill_forward",
+           "fq_init", "fq_dense_f16_tile", "fq_rope_table")
 
 
 def _check(rc: int) -> None:
@@ -101,6 +105,11 @@ def fq_last_error() -> str:
 
 def fq_version() -> str:
     return _lib.fq_version().decode()
+
+
+def fq_init() -> None:
+    """Prepare the library's kernels on the current device (needed before capturing calls into a graph)."""
+    _check(_lib.fq_init())
 
 
 # ------------------------------------------------------------------ host side
@@ -274,7 +283,8 @@ def fq_glue(op: int, a, b=None, c=None, out=None, stream=None):
     return out
 
 
-def fq_dense_f16(x, W, out=None, stream=None):
+def fq_dense_f16(x, W, out=None, stream=None, tile_rows: int = 0):
+    """tile_rows = 128 or 256 pins one of the two kernels (fq_dense_f16_tile); 0 lets the library choose."""
     torch = _torch()
     x = _dev(x, torch.float16, "x")
     W = _dev(W, torch.float16, "W")
@@ -284,7 +294,10 @@ def fq_dense_f16(x, W, out=None, stream=None):
         raise FqError(-2, f"x has K={K}, W has K={W.shape[1]}")
     if out is None:
         out = torch.empty((M, N), dtype=torch.float16, device=x.device)
-    _check(_lib.fq_dense_f16(_dp(x), M, _dp(W), N, K, _dp(out), _stream(stream)))
+    if tile_rows:
+        _check(_lib.fq_dense_f16_tile(_dp(x), M, _dp(W), N, K, _dp(out), tile_rows, _stream(stream)))
+    else:
+        _check(_lib.fq_dense_f16(_dp(x), M, _dp(W), N, K, _dp(out), _stream(stream)))
     return out
 
 
@@ -336,11 +349,12 @@ def fq_token_nll(logits, labels, out=None, stream=None):
 
 # ------------------------------------------------------------ real decoder blocks
 def rope_table(Tmax: int, head_dim: int = 128, base: float = 10000.0, device="cuda"):
-    """(cos, sin) of pos * base^(-2i/head_dim) as fp32 [Tmax, head_dim/2, 2] on the device (computed in
-    fp64 on the host, rounded once)."""
+    """(cos, sin) of pos * base^(-2i/head_dim) as fp32 [Tmax, head_dim/2, 2] on the device: the library's
+    host routine fq_rope_table fills it, this only uploads."""
     torch = _torch()
-    ang = np.arange(Tmax, dtype=np.float64)[:, None] * base ** (-2.0 * np.arange(head_dim // 2, dtype=np.float64) / head_dim)
-    return torch.from_numpy(np.stack([np.cos(ang), np.sin(ang)], axis=-1).astype(np.float32)).to(device)
+    table = np.empty((Tmax, head_dim // 2, 2), dtype=np.float32)
+    _check(_lib.fq_rope_table(Tmax, head_dim, float(base), _hp(table)))
+    return torch.from_numpy(table).to(device)
 
 
 def fq_attn_workspace_bytes(Tmax: int, n_heads: int) -> int:

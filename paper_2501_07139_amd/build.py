@@ -1,10 +1,17 @@
 """Build libfq.so (HIP kernels + C-ABI) for gfx950, in-tree.
 
     python paper_2501_07139_amd/build.py
+
+The decode kernel (fq_gemv.hip) waits for its input copies with a counted `s_waitcnt vmcnt(N)`: N vector
+loads of the weight ring are issued behind the copies and may stay in flight.  That count is a property of
+the compiled code, so the build compiles the file to assembly as well, checks every such wait against the
+loads the compiler actually placed (`check_gemv_waits`), and if one does not match rebuilds the file with
+-DFQ_GEMV_SAFE_WAIT, which orders the copies before the ring by a full wait instead.
 """
 from __future__ import annotations
 
 import os
+import re
 import subprocess
 import sys
 from concurrent.futures import ThreadPoolExecutor
@@ -32,12 +39,13 @@ def _hipcc() -> str:
     raise RuntimeError("hipcc not found")
 
 
-def _compile(src: str) -> str:
-    obj = os.path.join(OBJ, os.path.splitext(src)[0] + ".o")
-    cmd = [_hipcc(), *FLAGS, "-x", "hip", "-c", os.path.join(CSRC, src), "-o", obj]
+def _compile(src: str, extra=(), asm: bool = False) -> str:
+    obj = os.path.join(OBJ, os.path.splitext(src)[0] + (".s" if asm else ".o"))
+    mode = ["-S", "--cuda-device-only"] if asm else ["-c"]
+    cmd = [_hipcc(), *FLAGS, *extra, "-x", "hip", *mode, os.path.join(CSRC, src), "-o", obj]
     res = subprocess.run(cmd, capture_output=True, text=True)
-    noise = "is not a recognized feature for this target"
-    err = "\n".join(l for l in res.stderr.splitlines() if noise not in l)
+    noise = ("is not a recognized feature for this target", "argument unused during compilation")
+    err = "\n".join(l for l in res.stderr.splitlines() if not any(n in l for n in noise))
     if res.returncode != 0:
         raise RuntimeError(f"hipcc failed on {src}:\n{err}")
     if err.strip():
@@ -45,10 +53,57 @@ def _compile(src: str) -> str:
     return obj
 
 
+GEMV_WAIT_SITES = 7 * 2 * 6  # input modes x row counts x (2-bit whole/split, 3-bit whole/split, 4-bit, 8-bit)
+
+
+def check_gemv_waits(asm_text: str):
+    """Every stand-alone `s_waitcnt vmcnt(N)`, N > 0, directly ahead of a barrier in a gemv_stream_kernel must
+    have exactly N vector-memory operations between it and the copies into LDS.  Returns the mismatches."""
+    lines = asm_text.splitlines()
+    mem_op = re.compile(r"\b(global_load_|global_store|buffer_load|buffer_store|scratch_|flat_load|flat_store)")
+    kernel, found, bad = None, 0, []
+    for i, ln in enumerate(lines):
+        m = re.match(r"^(_ZN\S*gemv_stream_kernel\S*):", ln)
+        if m:
+            kernel = m.group(1)
+        if "s_endpgm" in ln:
+            kernel = None
+        m = re.search(r"s_waitcnt vmcnt\((\d+)\)\s*$", ln)
+        if not (m and kernel and int(m.group(1)) > 0):
+            continue
+        if "s_barrier" not in " ".join(lines[i + 1:i + 6]):
+            continue  # the compiler's own waits are not followed by the barrier
+        n, count, j = int(m.group(1)), 0, i - 1
+        while j > 0 and not lines[j].startswith("_ZN") and "global_load_lds" not in lines[j]:
+            count += bool(mem_op.search(lines[j]))
+            j -= 1
+        found += 1
+        if "global_load_lds" not in lines[j]:
+            bad.append("%s line %d: no copy into LDS ahead of the wait" % (kernel, i + 1))
+        elif count != n:
+            bad.append("%s line %d: vmcnt(%d) but %d loads issued behind the copies" % (kernel, i + 1, n, count))
+    if found != GEMV_WAIT_SITES:
+        bad.append("found %d counted waits, expected %d" % (found, GEMV_WAIT_SITES))
+    return bad
+
+
+WAIT_MODE = os.path.join(OBJ, "gemv_wait_mode.txt")  # "counted" or "safe": what the last build chose
+
+
 def build(verbose: bool = True) -> str:
     os.makedirs(OBJ, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
+    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES) + 1)) as ex:
+        asm_job = ex.submit(_compile, "fq_gemv.hip", (), True)
         objs = list(ex.map(_compile, SOURCES))
+        asm = asm_job.result()
+    with open(asm) as fh:
+        bad = check_gemv_waits(fh.read())
+    if bad:
+        sys.stderr.write("fq_gemv.hip: counted wait does not match the compiled code, building the safe order:\n  "
+                         + "\n  ".join(bad[:5]) + "\n")
+        _compile("fq_gemv.hip", ("-DFQ_GEMV_SAFE_WAIT",))
+    with open(WAIT_MODE, "w") as fh:
+        fh.write("safe\n" if bad else "counted\n")
     cmd = [_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:

@@ -88,7 +88,18 @@ extern "C" int fq_qlinear(const void *x, int M, const void *packed, const void *
     return qlinear_checked(x, M, w, out, static_cast<fq_stream>(stream));
 }
 
+extern "C" int fq_init(void)
+{
+    return check_hip(fq_gemv_prepare(), "fq_init");
+}
+
 extern "C" int fq_dense_f16(const void *x, int M, const void *W, int N, int K, void *out, void *stream)
+{
+    return fq_dense_f16_tile(x, M, W, N, K, out, 0, stream);
+}
+
+extern "C" int fq_dense_f16_tile(const void *x, int M, const void *W, int N, int K, void *out, int tile_rows,
+                                 void *stream)
 {
     if (!x || !W || !out)
         return fq_fail(FQ_ERR_NULL, "fq_dense_f16: NULL argument");
@@ -98,9 +109,9 @@ extern "C" int fq_dense_f16(const void *x, int M, const void *W, int N, int K, v
         return fq_fail(FQ_ERR_ALIGN, "fq_dense_f16: pointers must be 16-byte aligned");
     if (!below_4gib(M, K, 2) || !below_4gib(N, K, 2))
         return fq_fail(FQ_ERR_SHAPE, "fq_dense_f16: M=%d N=%d K=%d: x and W must each stay below 4 GiB", M, N, K);
-    // FQ_DENSE_TILE=128 or 256 in the environment pins the kernel (tests of either at any size)
-    const char *pin = getenv("FQ_DENSE_TILE");
-    const bool tiled = pin && *pin ? atoi(pin) == 256 : fq_dense_tiled_pays(M, N);
+    if (tile_rows != 0 && tile_rows != 128 && tile_rows != 256)
+        return fq_fail(FQ_ERR_SHAPE, "fq_dense_f16_tile: tile_rows=%d not in {0, 128, 256}", tile_rows);
+    const bool tiled = tile_rows ? tile_rows == 256 : fq_dense_tiled_pays(M, N);
     if (tiled)
         return check_hip(fq_launch_dense_tiled(x, M, W, N, K, out, static_cast<fq_stream>(stream)),
                          "fq_dense_f16 launch");
@@ -203,6 +214,9 @@ extern "C" size_t fq_stack_workspace_bytes(int M, int hidden, int ffn)
     return 10 * h + 3 * f;
 }
 
+static int stack_forward_checked(const fq_layer *layers, int L, const uint8_t *bitvec, const void *x_in, int M,
+                                 void *x_out, void *workspace, int H, int F, fq_stream st);
+
 extern "C" int fq_stack_forward(const fq_layer *layers, int L, const uint8_t *bitvec, const void *x_in, int M,
                                 void *x_out, void *workspace, size_t workspace_bytes, void *stream)
 {
@@ -213,14 +227,20 @@ extern "C" int fq_stack_forward(const fq_layer *layers, int L, const uint8_t *bi
     int H = 0, F = 0;
     if (int rc = validate_layers("fq_stack_forward", layers, L, bitvec, &H, &F))
         return rc;
-    fq_packed_ref sel[7];
     if (workspace_bytes < fq_stack_workspace_bytes(M, H, F))
         return fq_fail(FQ_ERR_WORKSPACE, "fq_stack_forward: workspace of %zu bytes, need %zu", workspace_bytes,
                        fq_stack_workspace_bytes(M, H, F));
     if (!aligned16(x_in) || !aligned16(x_out) || !aligned16(workspace))
         return fq_fail(FQ_ERR_ALIGN, "fq_stack_forward: x_in, x_out and workspace must be 16-byte aligned");
+    return stack_forward_checked(layers, L, bitvec, x_in, M, x_out, workspace, H, F, static_cast<fq_stream>(stream));
+}
 
-    fq_stream st = static_cast<fq_stream>(stream);
+// The launches of a stack forward; every argument has been validated and the workspace holds
+// fq_stack_workspace_bytes(M, H, F) bytes.
+static int stack_forward_checked(const fq_layer *layers, int L, const uint8_t *bitvec, const void *x_in, int M,
+                                 void *x_out, void *workspace, int H, int F, fq_stream st)
+{
+    fq_packed_ref sel[7];
     const size_t hb = align_up((size_t)M * H * 2), fb = align_up((size_t)M * F * 2);
     char *ws = static_cast<char *>(workspace);
     void *u = ws, *q = ws + hb, *k = ws + 2 * hb, *v = ws + 3 * hb, *a = ws + 4 * hb, *o = ws + 5 * hb,

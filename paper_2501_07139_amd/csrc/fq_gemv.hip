@@ -15,11 +15,15 @@
 //    across supertile rows, so the HBM stream never drains between rows.
 //  - The unpack is only the field extraction: a pair of codes becomes two fp16
 //    numbers 1024 + code*2^p by one and-or and goes to the matrix core as is.  The
-//    activations are staged in LDS already divided by 2^p (exact: a power of two),
-//    so the MFMA result is  sum_k x_k code_k + 1024 * sum_k x'_k.  The second term
-//    does not depend on the weight row: it is computed once per group while
-//    staging, together with sum_k x_k, and the group's contribution is
-//        scale * (P - 1024*sum x' - zero * sum x)
+//    activations are staged in LDS as x'_k = x_k * 2^(E - p): E is chosen per group
+//    of 128 so that the group's largest |x| lands in [2^14, 2^15), which keeps every
+//    value within 2^-20 of that maximum a normal fp16 number whatever the scale of
+//    the activations (without it, dividing small activations by 2^p would push them
+//    into the subnormal range and lose bits).  The MFMA result is
+//        P = 2^E * sum_k x_k code_k + 1024 * sum_k x'_k.
+//    The second term does not depend on the weight row: it is computed once per
+//    group while staging, together with sum_k x_k, and the group's contribution is
+//        scale * (2^-E * (P - 1024*sum x') - zero * sum x)
 //    in fp32: per weight there is neither a subtract nor a multiply, and any fp16
 //    zero (integer or not) is handled the same.
 //  - Bit-width dispatch happens once per workgroup; each bit-width has its own
@@ -216,22 +220,11 @@ struct GemvSlot {
     _Float16 scale[S], zero[S]; // of weight row lane % 16 of each sub-block
 };
 
-// 2^-pair_shift for element e of k-step s: the factor applied to x while staging.
+// pair_shift for element e of k-step s: staged x carries the factor 2^-shift against its group's scale.
 template <int BITS>
-__device__ __forceinline__ float stage_factor(int s, int e)
+__host__ __device__ constexpr int stage_shift(int s, int e)
 {
-    if constexpr (BITS == 8) {
-        return 1.0f;
-    } else if constexpr (BITS == 4) {
-        return ((e >> 1) & 1) ? 0.0625f : 1.0f;
-    } else if constexpr (BITS == 2) {
-        constexpr float f[8] = {1.0f, 0.25f, 0.0625f, 0.015625f, 0.00390625f, 1.0f, 0.25f, 0.0625f};
-        return f[4 * (s & 1) + (e >> 1)];
-    } else {
-        constexpr float f[16] = {1.0f, 0.125f, 0.015625f, 1.0f, 0.125f, 1.0f, 0.125f, 0.015625f,
-                                 1.0f, 0.125f, 1.0f, 0.125f, 0.015625f, 1.0f, 0.125f, 1.0f};
-        return f[4 * s + (e >> 1)];
-    }
+    return pair_shift<BITS>(4 * s + (e >> 1));
 }
 
 // Position in the stream of (work unit, group) items of one wavefront.
@@ -318,15 +311,46 @@ __device__ __forceinline__ h8 gemv_scaled(h8 v, float scale)
     return r;
 }
 
-// 2^-pair_shift of the eight elements of k-step s, as a packed constant
+// The shifts of the four pairs of k-step s, four bits each (pair v = e/2 in bits 4v..4v+3).
 template <int BITS>
-__device__ __forceinline__ h8 stage_factors(int s)
+__host__ __device__ constexpr uint32_t stage_shift_row(int s)
 {
-    h8 f;
+    return (uint32_t)stage_shift<BITS>(s, 0) | ((uint32_t)stage_shift<BITS>(s, 2) << 4) |
+           ((uint32_t)stage_shift<BITS>(s, 4) << 8) | ((uint32_t)stage_shift<BITS>(s, 6) << 12);
+}
+
+// x * 2^(E - pair_shift) for the eight elements of a chunk of k-step s: exact while the result is a normal
+// fp16 number, rounded to nearest below that.  s differs from lane to lane, so the row of shifts is
+// selected, not branched on.
+template <int BITS>
+__device__ __forceinline__ h8 stage_scaled(h8 x, int s, int E)
+{
+    constexpr uint32_t r0 = stage_shift_row<BITS>(0), r1 = stage_shift_row<BITS>(1), r2 = stage_shift_row<BITS>(2),
+                       r3 = stage_shift_row<BITS>(3);
+    const uint32_t row = s == 0 ? r0 : (s == 1 ? r1 : (s == 2 ? r2 : r3));
+    h8 w;
 #pragma unroll
     for (int e = 0; e < 8; ++e)
-        f[e] = (_Float16)stage_factor<BITS>(s, e);
-    return f;
+        w[e] = __builtin_ldexpf16(x[e], E - (int)((row >> (4 * (e >> 1))) & 15u));
+    return w;
+}
+
+// Largest |x| of a chunk as an fp16 bit pattern (positive fp16 numbers order like their bits), then over
+// each aligned run of 16 lanes (the 128 values of a group), in all of its lanes.
+__device__ __forceinline__ uint32_t group_max_bits(h8 x)
+{
+    const u4v v = __builtin_bit_cast(u4v, x) & 0x7fff7fffu;
+    uint32_t m = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const uint32_t d = i == 0 ? v.x : (i == 1 ? v.y : (i == 2 ? v.z : v.w));
+        m = max(m, max(d & 0xffffu, d >> 16));
+    }
+    m = max(m, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)m, 0xB1, 0xF, 0xF, true));
+    m = max(m, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)m, 0x4E, 0xF, 0xF, true));
+    m = max(m, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)m, 0x124, 0xF, 0xF, true));
+    m = max(m, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)m, 0x128, 0xF, 0xF, true));
+    return m;
 }
 
 // s_waitcnt immediate: vector-memory loads in flight <= n (n < 64), the other counters left alone
@@ -353,8 +377,9 @@ __device__ __forceinline__ void gemv_body(const GemvJob job, int bj, const GemvI
     const int GP = T * GNW;            // groups rounded up to whole turns of the wavefronts: the rest is zero
     h8 *xl = reinterpret_cast<h8 *>(smem);                                   // [GP*16][M] staged activations
     float *xsum = reinterpret_cast<float *>(smem + (size_t)GP * 16 * M * 16); // [GP][16] sum of x over the group
-    float *csum = xsum + (size_t)GP * 16;                                    // [GP][16] 1024 * sum of staged x
-    float *red = csum + (size_t)GP * 16;                                     // [2][GNW][S*MV][64]
+    float *csum = xsum + (size_t)GP * 16;                                    // [GP][16] 2^-E * 1024 * sum of staged x
+    float *esc = csum + (size_t)GP * 16;                                     // [GP][16] 2^-E of the group
+    float *red = esc + (size_t)GP * 16;                                      // [2][GNW][S*MV][64]
     h8 *raw = reinterpret_cast<h8 *>(red); // [NIN][trips][STEP] raw input row; free again before the first reduction
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -383,6 +408,11 @@ __device__ __forceinline__ void gemv_body(const GemvJob job, int bj, const GemvI
             __builtin_amdgcn_global_load_lds(src[i] + off, &raw[(i * trips + t) * STEP + 64 * wave], 16, 0, 0);
     }
     __builtin_amdgcn_sched_barrier(0); // the weights' loads stay behind the copies
+#ifdef FQ_GEMV_SAFE_WAIT
+    // Plain order: the copies land before any weight load is issued (costs the copies' latency per launch).
+    __builtin_amdgcn_s_waitcnt(FQ_WAIT_VMCNT0);
+    lds_barrier();
+#endif
 
     // ---- weights: unconditional loads (indices clamped into the matrix) so that a wavefront only
     // ever waits for the oldest slot of its ring.
@@ -528,12 +558,17 @@ __device__ __forceinline__ void gemv_body(const GemvJob job, int bj, const GemvI
             } else {
                 xe = gemv_scaled(v.f, inv1);
             }
-            const h8 w = xe * stage_factors<BITS>((kc >> 2) & 3); // exact: powers of two
+            // the group's exponent: its largest |x| (exponent field ex, taken as 1 for zero and subnormal
+            // maxima) is brought to 2^14: E = 29 - ex in [-1, 28]
+            const int ex = min(max((int)(group_max_bits(xe) >> 10), 1), 30), E = 29 - ex;
+            const h8 w = stage_scaled<BITS>(xe, (kc >> 2) & 3, E);
             xl[(size_t)kc * M + mm] = w;
             const float sx = row16_sum(gemv_sum(xe)), sc = row16_sum(gemv_sum(w));
             if ((kc & 15) == 0) {
+                const float einv = __builtin_bit_cast(float, (uint32_t)(127 - E) << 23); // 2^-E
                 xsum[(kc >> 4) * 16 + mm] = sx;
-                csum[(kc >> 4) * 16 + mm] = 1024.0f * sc;
+                csum[(kc >> 4) * 16 + mm] = einv * (1024.0f * sc); // exact scaling
+                esc[(kc >> 4) * 16 + mm] = einv;
             }
         };
         if (has0)
@@ -547,8 +582,13 @@ __device__ __forceinline__ void gemv_body(const GemvJob job, int bj, const GemvI
     };
     // Row 0 apart from the others: its copies were issued before the weights, so waiting for them leaves
     // the weights in flight; later rows are fetched behind the weights and wait for everything.
+#ifndef FQ_GEMV_SAFE_WAIT
+    // Counted wait: exactly the ring's RING_LOADS vector loads were issued behind the copies, so waiting until
+    // no more than that many are in flight means the copies have landed.  The build checks the count against
+    // the compiled code and falls back to FQ_GEMV_SAFE_WAIT when it does not hold.
     __builtin_amdgcn_s_waitcnt(gemv_wait_vmcnt(RING_LOADS)); // the copies of row 0 have landed ...
     lds_barrier();                                           // ... in every wavefront
+#endif
     // Zero what no row writes: the groups past K (items on them then add nothing) and the sums of the
     // activation rows past M.
     for (int i = chunks * M + tid; i < GP * 16 * M; i += STEP)
@@ -557,6 +597,7 @@ __device__ __forceinline__ void gemv_body(const GemvJob job, int bj, const GemvI
         if ((i & 15) >= M || (i >> 4) >= G) {
             xsum[i] = 0.f;
             csum[i] = 0.f;
+            esc[i] = 0.f;
         }
     stage_row(0);
     for (int mm = 1; mm < M; ++mm) {
@@ -602,18 +643,21 @@ __device__ __forceinline__ void gemv_body(const GemvJob job, int bj, const GemvI
 #pragma unroll
                 for (int s = 0; s < 4; ++s)
                     ax[s] = xg_ptr[s * 4 * M];
-                float xg[MV], cg[MV];
+                float xg[MV], cg[MV], eg[MV];
                 if constexpr (MV == 4) {
                     const f4 a4 = *reinterpret_cast<const f4 *>(xsum + g * 16 + 4 * c);
                     const f4 c4 = *reinterpret_cast<const f4 *>(csum + g * 16 + 4 * c);
+                    const f4 e4 = *reinterpret_cast<const f4 *>(esc + g * 16 + 4 * c);
 #pragma unroll
                     for (int v = 0; v < 4; ++v) {
                         xg[v] = a4[v];
                         cg[v] = c4[v];
+                        eg[v] = e4[v];
                     }
                 } else {
                     xg[0] = xsum[g * 16];
                     cg[0] = csum[g * 16];
+                    eg[0] = esc[g * 16];
                 }
 #pragma unroll
                 for (int u = 0; u < S; ++u) {
@@ -635,11 +679,12 @@ __device__ __forceinline__ void gemv_body(const GemvJob job, int bj, const GemvI
 #pragma unroll
                     for (int s = 0; s < 4; ++s)
                         p = mfma16x16x32(ax[s], make_h8_bits(h[4 * s], h[4 * s + 1], h[4 * s + 2], h[4 * s + 3]), p);
-                    // p = sum x code + 1024 sum x': take the bias and zero * sum x away, then scale
+                    // p = 2^E sum x code + 1024 sum x': back to the scale of x (exact), take the bias and
+                    // zero * sum x away, then scale
                     const float zf = (float)ring[d].zero[u], sf = (float)ring[d].scale[u];
 #pragma unroll
                     for (int v = 0; v < MV; ++v)
-                        acc[u][v] = fmaf(sf, p[v] - fmaf(zf, xg[v], cg[v]), acc[u][v]);
+                        acc[u][v] = fmaf(sf, fmaf(eg[v], p[v], -fmaf(zf, xg[v], cg[v])), acc[u][v]);
                 }
             }
             issue(ring[d]); // the item D places ahead reuses this slot
@@ -722,7 +767,7 @@ GemvKernel gemv_kernel_for(int mode, int M, int *slot)
 
 constexpr size_t GEMV_MAX_LDS = 152 * 1024;
 
-// Dynamic LDS of a streaming launch: staged x and the group sums (groups rounded up to whole turns of
+// Dynamic LDS of a streaming launch: staged x, the group sums and exponents (groups rounded up to whole turns of
 // the wavefronts), and one region shared by the raw input row (inputs of the mode, whole trips of 512
 // chunks) and the reduction buffers.
 size_t gemv_stream_lds(int M, int K, int bits, int inputs)
@@ -731,64 +776,95 @@ size_t gemv_stream_lds(int M, int K, int bits, int inputs)
     const size_t gp = (size_t)(((K >> 7) + GNW - 1) / GNW) * GNW;
     const size_t red = 2 * (size_t)GNW * sub * mv * 64 * 4;
     const size_t raw = (size_t)inputs * (((K >> 3) + 64 * GNW - 1) / (64 * GNW)) * (64 * GNW) * 16;
-    return gp * 16 * M * 16 + 2 * gp * 16 * 4 + (red > raw ? red : raw);
+    return gp * 16 * M * 16 + 3 * gp * 16 * 4 + (red > raw ? red : raw);
 }
 
 int rows_per_supertile(int bits) { return bits == 2 ? 32 : (bits == 3 ? 64 : 16); }
 
-// Resident workgroups of a streaming kernel on the current device for a request of dynamic LDS.  What is
-// learnt (the CU count, that a kernel's LDS limit has been raised, the last few answers) is kept per device
-// and guarded, so that callers on several threads or devices do not trip over each other.
-int gemv_resident_blocks(GemvKernel kernel, int slot, size_t lds, int *out)
+// What a launch needs to know about the device, learnt once per device by fq_gemv_prepare (fq_init, or the
+// first launch on that device): the CU count, and for each of the 14 kernel variants the largest dynamic-LDS
+// request that still leaves p workgroups resident per CU.  Nothing on the launch path then sets attributes
+// or queries the runtime, so launches can be captured into a graph.
+constexpr int GEMV_VARIANTS = 14, GEMV_MAX_PER_CU = 4;
+struct GemvDevice {
+    bool ready = false;
+    int cus = 0;
+    size_t max_lds[GEMV_VARIANTS][GEMV_MAX_PER_CU + 1] = {}; // [slot][p]: largest request with >= p resident
+};
+GemvDevice g_gemv_dev[16];
+std::mutex g_gemv_guard;
+
+int gemv_prepare_locked(GemvDevice &d, int dev)
 {
-    struct PerDevice {
-        int cus = 0;
-        bool prepared[14] = {};
-        size_t seen_lds[14][4] = {};
-        int seen_blocks[14][4] = {}, seen[14] = {};
-    };
-    static PerDevice table[16];
-    static std::mutex guard;
+    int n = 0;
+    hipError_t e = hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e != hipSuccess)
+        return (int)e;
+    for (int mode = 0; mode < 7; ++mode)
+        for (int wide = 0; wide < 2; ++wide) {
+            int slot = 0;
+            const GemvKernel kernel = gemv_kernel_for(mode, wide ? 16 : 1, &slot);
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    (int)GEMV_MAX_LDS);
+            if (e != hipSuccess)
+                return (int)e;
+            for (int p = 1; p <= GEMV_MAX_PER_CU; ++p) {
+                // occupancy falls as the request grows: bisect for the last request (in KiB) with >= p resident
+                int lo = -1, hi = (int)(GEMV_MAX_LDS >> 10) + 1;
+                while (hi - lo > 1) {
+                    const int mid = (lo + hi) / 2;
+                    int per_cu = 0;
+                    e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, 64 * GNW, (size_t)mid << 10);
+                    if (e != hipSuccess)
+                        return (int)e;
+                    if (per_cu >= p)
+                        lo = mid;
+                    else
+                        hi = mid;
+                }
+                d.max_lds[slot][p] = lo < 0 ? 0 : (size_t)lo << 10;
+            }
+        }
+    d.cus = n;
+    d.ready = true;
+    return 0;
+}
+
+// Resident workgroups of variant `slot` on the current device for a request of dynamic LDS.
+int gemv_resident_blocks(int slot, size_t lds, int *out)
+{
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess)
         return (int)e;
     if (dev < 0 || dev >= 16)
         return (int)hipErrorInvalidDevice;
-    std::lock_guard<std::mutex> lock(guard);
-    PerDevice &d = table[dev];
-    if (d.cus == 0) {
-        int n = 0;
-        e = hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev);
-        if (e != hipSuccess)
-            return (int)e;
-        d.cus = n;
-    }
-    if (!d.prepared[slot]) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)GEMV_MAX_LDS);
-        if (e != hipSuccess)
-            return (int)e;
-        d.prepared[slot] = true;
-    }
-    for (int i = 0; i < d.seen[slot]; ++i)
-        if (d.seen_lds[slot][i] == lds) {
-            *out = d.seen_blocks[slot][i];
-            return 0;
-        }
-    int per_cu = 0;
-    e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, 64 * GNW, lds);
-    if (e != hipSuccess)
-        return (int)e;
-    *out = d.cus * (per_cu > 0 ? per_cu : 1);
-    if (d.seen[slot] < 4) {
-        d.seen_lds[slot][d.seen[slot]] = lds;
-        d.seen_blocks[slot][d.seen[slot]++] = *out;
-    }
+    std::lock_guard<std::mutex> lock(g_gemv_guard);
+    GemvDevice &d = g_gemv_dev[dev];
+    if (!d.ready)
+        if (int rc = gemv_prepare_locked(d, dev))
+            return rc;
+    int per_cu = 1;
+    for (int p = 2; p <= GEMV_MAX_PER_CU; ++p)
+        if (lds <= d.max_lds[slot][p])
+            per_cu = p;
+    *out = d.cus * per_cu;
     return 0;
 }
 
 } // namespace
+
+int fq_gemv_prepare()
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess)
+        return (int)e;
+    if (dev < 0 || dev >= 16)
+        return (int)hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_gemv_guard);
+    return g_gemv_dev[dev].ready ? 0 : gemv_prepare_locked(g_gemv_dev[dev], dev);
+}
 
 bool fq_gemv_can_stream(int M, int K, int bits, int inputs)
 {
@@ -813,7 +889,7 @@ int fq_launch_gemv_multi(const fq_gemv_input &src, int M, const fq_packed_ref *w
     }
     int slot = 0, resident = 0;
     const GemvKernel kernel = gemv_kernel_for(src.mode, M, &slot);
-    if (int e = gemv_resident_blocks(kernel, slot, lds, &resident))
+    if (int e = gemv_resident_blocks(slot, lds, &resident))
         return e;
     // Work units.  Whole supertile rows as a rule; but when even the 16-row sub-blocks of the 2- and 3-bit
     // matrices (2 or 4 per supertile row) are no more than the resident workgroups, those matrices are

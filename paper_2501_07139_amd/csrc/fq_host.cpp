@@ -267,3 +267,23 @@ extern "C" int fq_pack_groups(const uint8_t *codes, const uint16_t *scales, cons
         }
     return FQ_OK;
 }
+
+// Rotary-embedding table of the real decoder blocks: angles pos * base^(-2i/head_dim) in fp64, their cosine
+// and sine rounded once to fp32.
+extern "C" int fq_rope_table(int Tmax, int head_dim, double base, float *out)
+{
+    if (!out)
+        return fq_fail(FQ_ERR_NULL, "fq_rope_table: NULL output");
+    if (Tmax <= 0 || head_dim <= 0 || head_dim % 2 != 0 || !(base > 0.0))
+        return fq_fail(FQ_ERR_SHAPE, "fq_rope_table: Tmax=%d head_dim=%d base=%g", Tmax, head_dim, base);
+    const int half = head_dim / 2;
+    parallel_rows(Tmax, [&](int lo, int hi) {
+        for (int t = lo; t < hi; ++t)
+            for (int i = 0; i < half; ++i) {
+                const double ang = (double)t * std::pow(base, -2.0 * (double)i / (double)head_dim);
+                out[((size_t)t * half + i) * 2 + 0] = (float)std::cos(ang);
+                out[((size_t)t * half + i) * 2 + 1] = (float)std::sin(ang);
+            }
+    });
+    return FQ_OK;
+}

@@ -34,6 +34,8 @@ struct fq_gemv_input {
 };
 // inputs: how many of a, b, c the mode reads (mode 2: three, modes 3 to 6: two, else one)
 bool fq_gemv_can_stream(int M, int K, int bits, int inputs);
+// Once per device: raises the streaming kernels' LDS limit and learns their residency (idempotent).
+int fq_gemv_prepare();
 int fq_launch_gemv_multi(const fq_gemv_input &src, int M, const fq_packed_ref *w, void *const *outs, int count,
                          fq_stream st);
 int fq_launch_gemm(const void *x, int M, const fq_packed_ref &w, void *out, fq_stream st);

@@ -96,7 +96,29 @@ def test_resident_model_follows_the_budget_and_matches_a_fully_resident_stack():
         want = fq.fq_stack_forward(full, np.asarray(path[i], dtype=np.uint8), x)
         return torch.equal(got.view(torch.int16), want.view(torch.int16))
 
+    deq = {}
+
+    def oracle_agrees(i, M):
+        """The hosted member against the oracle's stack of that member's stored widths (Section "Transition
+        Granularity": after the replacements the model IS member i), at the stack tolerance."""
+        xh = fq_synth.activations(801 + M, M, sh["hidden"])
+        mats = []
+        for l in range(L):
+            row = []
+            for j in range(7):
+                b = path[i][7 * l + j]
+                if (l, j, b) not in deq:
+                    deq[(l, j, b)] = oracle.dequant(*quantized[l][j][b])
+                row.append(deq[(l, j, b)])
+            mats.append(row)
+        want = oracle.stack_forward(xh, mats).astype(np.float64)
+        got = model.forward(torch.from_numpy(xh.view(np.int16)).cuda().view(torch.float16))
+        got = got.cpu().view(torch.int16).numpy().view(np.float16).astype(np.float64)
+        d = np.abs(got - want)
+        return d.max() <= 2e-2 and d.mean() <= 2e-3
+
     assert model.resident_bytes() == model.footprints[0] and same(0, 1) and same(0, 40)
+    assert oracle_agrees(0, 1) and oracle_agrees(0, 24)
     # shrink the budget step by step: the hosted member is always the largest that fits
     for budget in (model.footprints[5], model.footprints[20] + 1, model.footprints[-1]):
         i = model.set_budget(budget)
@@ -104,6 +126,7 @@ def test_resident_model_follows_the_budget_and_matches_a_fully_resident_stack():
         assert model.resident_bytes() == model.footprints[i] <= budget
         assert tuple(int(b) for b in model.bitvec) == path[i]
         assert same(i, 1) and same(i, 40)
+        assert oracle_agrees(i, 1) and oracle_agrees(i, 24)
     # swap by swap the transitional memory is one packing
     assert model.peak_extra_bytes <= max(search.footprint_bytes((b,), [s]) for s in shapes for b in levels)
     # memory comes back: grow again
@@ -116,6 +139,7 @@ def test_resident_model_follows_the_budget_and_matches_a_fully_resident_stack():
         model.begin_move(13)
     model.commit()
     assert model.index == 12 and model.resident_bytes() == model.footprints[12] and same(12, 1) and same(12, 40)
+    assert oracle_agrees(12, 1) and oracle_agrees(12, 24)
     # a non-resident width is refused by the library, not silently served
     bad = np.asarray(path[0], dtype=np.uint8)
     x = torch.zeros((1, sh["hidden"]), dtype=torch.float16, device="cuda")

@@ -181,17 +181,15 @@ def test_more_bits_track_the_unquantized_layer_better_on_gpu(fq, torch):
 
 
 # --------------------------------------------------------------- dense head
-@pytest.mark.parametrize("tile", ["auto", "128", "256"])
+@pytest.mark.parametrize("tile", [0, 128, 256])
 @pytest.mark.parametrize("case", [(40, 512, 256), (300, 1000, 384), (257, 1026, 128), (2048, 32000, 512)], ids=str)
-def test_dense_head_against_oracle(fq, torch, case, tile, monkeypatch):
-    """Both kernels behind fq_dense_f16 (128- and 256-row tiles), pinned through the environment, and the
+def test_dense_head_against_oracle(fq, torch, case, tile):
+    """Both kernels behind fq_dense_f16 (128- and 256-row tiles), pinned through fq_dense_f16_tile, and the
     library's own choice; ragged sizes cover rows and columns past the last full tile."""
     M, N, K = case
-    if tile != "auto":
-        monkeypatch.setenv("FQ_DENSE_TILE", tile)
     X = fq_synth.activations(13, M, K)
     W = fq_synth.weights(14, N, K).astype(np.float16)
-    y = host16(fq.fq_dense_f16(dev(torch, X), dev(torch, W)))
+    y = host16(fq.fq_dense_f16(dev(torch, X), dev(torch, W), tile_rows=tile))
     if M * N > 1 << 20:
         rng = np.random.default_rng(0)
         rows = np.unique(np.concatenate([rng.integers(0, M, 40), [0, M - 1]]))
@@ -552,3 +550,164 @@ def test_tree_search_on_the_gpu_makes_choices_the_oracle_agrees_with(fq, torch):
         for b in kept:                                  # nothing kept is clearly worse than the oracle's cut
             assert want[b] <= cut * (1 + 4e-3)
 
+
+
+# ------------------------------------- the hot path's own unpack, bit for bit
+def _random_packing(fq, seed, N, K, bits, fractional):
+    """Random codes, positive fp16 scales, and zeros that are integers (what the quantizer stores) or
+    integers over a power of two (what truncating code bits leaves: Section "Elastic Serving")."""
+    codes = fq_synth.codes(seed, N, K, bits)
+    G = K // 128
+    s = (np.abs(fq_synth.activations(seed + 1, N, G).astype(np.float32)) * 0.01 + 2e-3).astype(np.float16)
+    zi = fq_synth.codes(seed + 2, N, G, bits).astype(np.float32)
+    z = (zi / (1 << (8 - bits)) if fractional and bits < 8 else (zi / 4 if fractional else zi)).astype(np.float16)
+    return fq.PackedMatrix.from_host(codes, s, z, bits), oracle.dequant(codes, s, z)
+
+
+@pytest.mark.parametrize("fractional", [False, True], ids=["int_zero", "frac_zero"])
+@pytest.mark.parametrize("bits", BITS)
+@pytest.mark.parametrize("shape", [(4096, 512), (11008, 1536), (200, 640)], ids=lambda s: "N%d_K%d" % s)
+def test_gemm_unpack_is_bit_exact_through_an_identity(fq, torch, bits, shape, fractional):
+    """X = I_K, M = K: the matrix-core kernel must return its own dequantized weights, rounded once to
+    fp16, transposed: out[m, n] = fp16(scale * (code - zero))[n, m], every other term being an exact zero.
+    N = 4096 runs the 128-wide tiles, N = 11008 with M = 1536 the 256-wide ones (2 and 4 bits); N = 200 ends
+    in a ragged tile."""
+    N, K = shape
+    w, W32 = _random_packing(fq, 900 + bits, N, K, bits, fractional)
+    X = np.eye(K, dtype=np.float16)
+    y = host16(fq.fq_qlinear(dev(torch, X), w))
+    want = oracle.round_f16(W32.astype(np.float64)).T
+    assert y.shape == want.shape
+    assert np.array_equal(y.view(np.uint16), np.ascontiguousarray(want).view(np.uint16))
+
+
+@pytest.mark.parametrize("fractional", [False, True], ids=["int_zero", "frac_zero"])
+@pytest.mark.parametrize("bits", BITS)
+@pytest.mark.parametrize("M", [1, 16])
+@pytest.mark.parametrize("shape", [(4096, 4096), (11008, 4096), (96, 512), (4096, 11008)], ids=lambda s: "N%d_K%d" % s)
+def test_gemv_unpack_is_bit_exact_on_one_hot_rows(fq, torch, bits, M, shape, fractional):
+    """One-hot activations: the decode kernel must return single dequantized weights rounded once to fp16
+    (bias, group exponent and zero all leave exactly).  4096 x 4096 at 2 and 3 bits runs the sub-block work
+    units, the other shapes whole supertile rows; the positions walk through all 128 places of a group and
+    through different groups."""
+    N, K = shape
+    w, W32 = _random_packing(fq, 950 + bits, N, K, bits, fractional)
+    want16 = oracle.round_f16(W32.astype(np.float64))
+    G = K // 128
+    for t in range(0, 128, 16 if M == 16 else 37):
+        ks = [((5 * t + 7 * m) % G) * 128 + (t + m) % 128 for m in range(M)]
+        X = np.zeros((M, K), dtype=np.float16)
+        X[np.arange(M), ks] = 1.0
+        y = host16(fq.fq_qlinear(dev(torch, X), w))
+        want = np.ascontiguousarray(want16[:, ks].T)
+        assert np.array_equal(y.view(np.uint16), want.view(np.uint16)), (t, ks[:3])
+
+
+@pytest.mark.parametrize("bits", BITS)
+@pytest.mark.parametrize("M", [1, 16])
+@pytest.mark.parametrize("scale", [1e-2, 1e-3, 1e-4, 30.0])
+def test_gemv_keeps_its_accuracy_for_small_and_large_activations(fq, torch, bits, M, scale):
+    """The decode kernel stages x times a power of two per bit field; a per-group exponent keeps the staged
+    values normal fp16 numbers, so the 2e-3 bar holds whatever the scale of the activations (fq_qlinear takes
+    any fp16 x), as it does for the matrix-core kernel at M = 17."""
+    N, K = 512, 4096
+    w, codes, s, z = make_matrix(fq, 120 + bits, N, K, bits)
+    W32 = oracle.dequant(codes, s, z)
+    for rows in (M, 17):
+        X = (fq_synth.activations(19, rows, K).astype(np.float32) * scale).astype(np.float16)
+        X[0, 5] = np.float16(scale * 50.0)          # an outlier inside one group
+        y = host16(fq.fq_qlinear(dev(torch, X), w))
+        assert qerr(y, oracle.qlinear(X, W32)) <= TOL, rows
+
+
+@pytest.mark.parametrize("bits", BITS)
+def test_quantize_pack_qlinear_from_the_librarys_own_quantizer(fq, torch, bits):
+    """Row a1 end to end: fp32 weights -> fq_quantize_rtn -> fq_pack_groups -> fq_qlinear, against the oracle's
+    own quantizer, dequantizer and product from the same weights."""
+    N, K = 300, 1024
+    W = fq_synth.weights(140 + bits, N, K)
+    codes, s, z = fq.fq_quantize_rtn(W, bits)
+    oc, os_, oz = oracle.quantize_rtn(W, bits)
+    assert np.array_equal(codes, oc) and np.array_equal(s.view(np.uint16), os_.view(np.uint16))
+    assert np.array_equal(z.view(np.uint16), oz.view(np.uint16))
+    w = fq.PackedMatrix.from_host(codes, s, z, bits)
+    W32 = oracle.dequant(oc, os_, oz)
+    assert np.array_equal(fq.fq_dequant(w).cpu().numpy().view(np.uint32), W32.view(np.uint32))
+    for M in (1, 7, 48):
+        X = fq_synth.activations(141, M, K)
+        assert qerr(host16(fq.fq_qlinear(dev(torch, X), w)), oracle.qlinear(X, W32)) <= TOL, M
+
+
+# ---------------------------------------------- guard bytes around every buffer
+class Guarded:
+    """A device buffer of `nbytes` with 4 KiB of a known pattern on either side."""
+    PAD = 4096
+
+    def __init__(self, torch, nbytes, fill=0xA5):
+        self.torch, self.n = torch, nbytes
+        self.raw = torch.full((nbytes + 2 * self.PAD,), fill, dtype=torch.uint8, device="cuda")
+        self.fill = fill
+
+    def bytes(self):
+        return self.raw[self.PAD:self.PAD + self.n]
+
+    def half(self, *shape):
+        return self.bytes().view(self.torch.float16).view(*shape)
+
+    def f32(self, *shape):
+        return self.bytes().view(self.torch.float32).view(*shape)
+
+    def intact(self):
+        lo, hi = self.raw[:self.PAD], self.raw[self.PAD + self.n:]
+        return bool((lo == self.fill).all().item()) and bool((hi == self.fill).all().item())
+
+
+@pytest.mark.parametrize("bits", BITS)
+@pytest.mark.parametrize("case", [(1, 70, 256), (5, 200, 384), (16, 96, 11008), (33, 70, 256), (300, 200, 384),
+                                  (129, 1030, 512)], ids=lambda c: "M%d_N%d_K%d" % c)
+def test_qlinear_writes_only_its_output(fq, torch, bits, case):
+    """Ragged M and N: nothing outside out[M, N] is written, and what is written matches the oracle."""
+    M, N, K = case
+    w, codes, s, z = make_matrix(fq, 160 + bits, N, K, bits)
+    X = fq_synth.activations(161, M, K)
+    out = Guarded(torch, M * N * 2)
+    fq.fq_qlinear(dev(torch, X), w, out=out.half(M, N))
+    torch.cuda.synchronize()
+    assert out.intact()
+    assert qerr(host16(out.half(M, N)), oracle.qlinear(X, oracle.dequant(codes, s, z))) <= TOL
+
+
+@pytest.mark.parametrize("M", [1, 3, 40])
+def test_stack_forward_stays_inside_output_and_workspace(fq, torch, M):
+    """The workspace bound fq_stack_workspace_bytes is exact: one byte less is refused, and with exactly that
+    many bytes nothing beyond the workspace or the output is touched."""
+    stack, host, sh = build_stack(fq, "tiny", 330)
+    bitvec = fq_synth.bit_vector(3, 7 * sh["layers"], probs=(0.25, 0.25, 0.25, 0.25))
+    x = dev(torch, fq_synth.activations(331, M, sh["hidden"]))
+    need = fq.fq_stack_workspace_bytes(M, sh["hidden"], sh["ffn"])
+    ws, out = Guarded(torch, need), Guarded(torch, M * sh["hidden"] * 2)
+    got = fq.fq_stack_forward(stack, bitvec, x, out=out.half(M, sh["hidden"]), workspace=ws.bytes())
+    torch.cuda.synchronize()
+    assert ws.intact() and out.intact()
+    want = fq.fq_stack_forward(stack, bitvec, x)
+    assert torch.equal(got.view(torch.int16), want.view(torch.int16))
+    with pytest.raises(fq.FqError) as e:
+        fq.fq_stack_forward(stack, bitvec, x, workspace=ws.bytes()[:need - 1])
+    assert e.value.code == -6
+
+
+@pytest.mark.parametrize("case", [(300, 1001, 256), (5, 70, 128), (257, 513, 384)], ids=str)
+def test_head_nll_stays_inside_output_and_workspace(fq, torch, case):
+    M, V, K = case
+    X = dev(torch, fq_synth.activations(171, M, K))
+    W = dev(torch, fq_synth.weights(172, V, K, 0.05, 99).astype(np.float16))
+    lab = dev(torch, fq_synth.labels(173, M, V))
+    need = fq.fq_head_nll_workspace_bytes(M, V)
+    ws, out = Guarded(torch, need), Guarded(torch, M * 4)
+    got = fq.fq_head_nll(X, W, lab, out=out.f32(M), workspace=ws.bytes())
+    torch.cuda.synchronize()
+    assert ws.intact() and out.intact()
+    assert torch.equal(got, fq.fq_head_nll(X, W, lab))
+    with pytest.raises(fq.FqError) as e:
+        fq.fq_head_nll(X, W, lab, workspace=ws.bytes()[:need - 16])
+    assert e.value.code == -6

@@ -167,3 +167,26 @@ def test_bench_refuses_more_than_one_gpu():
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
     r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
     assert r.returncode != 0 and "one GPU" in (r.stdout + r.stderr)
+
+
+def test_rope_table_against_the_closed_form():
+    """fq_rope_table: (cos, sin) of pos * base^(-2i/d), fp64 rounded once to fp32."""
+    Tmax, d = 300, 128
+    table = np.empty((Tmax, d // 2, 2), dtype=np.float32)
+    rc = fq._lib.fq_rope_table(Tmax, d, 10000.0, table.ctypes.data_as(ctypes.c_void_p))
+    assert rc == 0
+    ang = np.arange(Tmax, dtype=np.float64)[:, None] * 10000.0 ** (-2.0 * np.arange(d // 2, dtype=np.float64) / d)
+    # pow and ** may differ in the last place of the fp64 angle: one fp32 ulp of slack, exact almost everywhere
+    assert np.max(np.abs(table[..., 0] - np.cos(ang))) <= 2.0 ** -23
+    assert np.max(np.abs(table[..., 1] - np.sin(ang))) <= 2.0 ** -23
+    assert np.array_equal(table[0, :, 0], np.ones(d // 2, dtype=np.float32)) and not table[0, :, 1].any()
+    assert np.allclose(table[..., 0].astype(np.float64) ** 2 + table[..., 1].astype(np.float64) ** 2, 1.0, atol=3e-7)
+    assert fq._lib.fq_rope_table(0, d, 10000.0, table.ctypes.data_as(ctypes.c_void_p)) == -2
+    assert fq._lib.fq_rope_table(4, 7, 10000.0, table.ctypes.data_as(ctypes.c_void_p)) == -2
+    assert fq._lib.fq_rope_table(4, d, 10000.0, None) == -1
+
+
+def test_dense_tile_argument_is_validated_on_the_host():
+    one = ctypes.c_void_p(16)
+    assert fq._lib.fq_dense_f16_tile(one, 4, one, 4, 128, one, 64, None) == -2
+    assert "tile_rows" in fq.fq_last_error()
