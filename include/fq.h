@@ -182,6 +182,22 @@ int fq_stack_forward(const fq_layer *layers, int L, const uint8_t *bitvec,
                      const void *x_in, int M, void *x_out,
                      void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * fq_stack_forward for callers that cannot allocate or hold a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * computation and the same kernels, for M <= 16 rows and hidden, ffn <= 16384, with
+ * the activations between the launches kept in a 6.5 MiB array that is part of the
+ * library's device code (every GPU the library runs on holds it until the process
+ * ends).  The call allocates nothing, on the device or through any library; larger
+ * M or wider blocks are refused with FQ_ERR_SHAPE.  Every call on a GPU uses that
+ * GPU's one array: calls that overlap in time on the same GPU (two streams, two
+ * threads) race and must be serialised by the caller; nothing in the array has to
+ * survive from one call to the next.  Call fq_init() first if the call is to be
+ * captured.
+ */
+int fq_stack_forward_noalloc(const fq_layer *layers, int L, const uint8_t *bitvec,
+                             const void *x_in, int M, void *x_out, void *stream);
+
 /* Single glue steps of the block above, exposed for layer-by-layer parity checks.
  * All tensors fp16 [M,H] row-major on the device; b and c may be NULL where unused.
  *   op 0: out = rms(a)              op 1: out = rms(a + b + c)

@@ -60,6 +60,7 @@ def _load() -> ctypes.CDLL:
         "fq_qlinear": (ci, [vp, ci, vp, vp, vp, ci, ci, ci, ci, vp, vp]),
         "fq_stack_workspace_bytes": (sz, [ci, ci, ci]),
         "fq_stack_forward": (ci, [ctypes.POINTER(fq_layer), ci, vp, vp, ci, vp, vp, sz, vp]),
+        "fq_stack_forward_noalloc": (ci, [ctypes.POINTER(fq_layer), ci, vp, vp, ci, vp, vp]),
         "fq_glue": (ci, [ci, vp, vp, vp, ci, ci, vp, vp]),
         "fq_init": (ci, []),
         "fq_dense_f16": (ci, [vp, ci, vp, ci, ci, vp, vp]),
@@ -91,7 +92,7 @@ EXPORTS = ("fq_last_error", "fq_version", "fq_quantize_rtn", "fq_packed_bytes", 
            "fq_token_nll", "fq_logit_l2", "fq_head_nll_workspace_bytes", "fq_head_nll",
            "fq_attn_workspace_bytes", "fq_decode_workspace_bytes", "fq_attn_decode", "fq_decode_step",
            "fq_attn_prefill_workspace_bytes", "fq_prefill_workspace_bytes", "fq_attn_prefill", "fq_prefill_forward",
-           "fq_init", "fq_dense_f16_tile", "fq_rope_table")
+           "fq_init", "fq_dense_f16_tile", "fq_rope_table", "fq_stack_forward_noalloc")
 
 
 def _check(rc: int) -> None:
@@ -270,6 +271,19 @@ def fq_stack_forward(stack: Stack, bitvec, x, out=None, workspace=None, stream=N
         workspace = torch.empty(fq_stack_workspace_bytes(M, stack.hidden, stack.ffn), dtype=torch.uint8, device=x.device)
     _check(_lib.fq_stack_forward(stack.table, stack.L, _hp(bitvec), _dp(x), M, _dp(out), _dp(workspace),
                                  workspace.numel(), _stream(stream)))
+    return out
+
+
+def fq_stack_forward_noalloc(stack: Stack, bitvec, x, out, stream=None):
+    """fq_stack_forward on the library's own static scratch (M <= 16); `out` is the caller's."""
+    torch = _torch()
+    x = _dev(x, torch.float16, "x")
+    out = _dev(out, torch.float16, "out")
+    bitvec = _np(np.asarray(bitvec, dtype=np.uint8), np.uint8)
+    if bitvec.size != 7 * stack.L:
+        raise FqError(-2, f"bitvec has {bitvec.size} entries, stack needs {7 * stack.L}")
+    _check(_lib.fq_stack_forward_noalloc(stack.table, stack.L, _hp(bitvec), _dp(x), x.shape[0], _dp(out),
+                                         _stream(stream)))
     return out
 
 

@@ -7,6 +7,16 @@
 
 #include <hip/hip_runtime.h>
 
+#include <mutex>
+
+// Scratch of the entry point that must not allocate (fq_stack_forward_noalloc): the activations of a decode
+// stack forward for up to 16 rows of up to 16384 elements.  Every device the library runs on holds its own
+// copy of this array until the process ends.  In host code the array's name is only a handle: the device
+// address comes from hipGetSymbolAddress (static_scratch below) and is what kernels and copies are given.
+constexpr int kNoallocMaxM = 16, kNoallocMaxDim = 16384;
+constexpr size_t kNoallocScratchBytes = (size_t)13 * kNoallocMaxM * kNoallocMaxDim * 2;
+static __device__ __align__(256) unsigned char scratch[kNoallocScratchBytes];
+
 namespace {
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -60,6 +70,31 @@ constexpr int kMaxGlueH = 16384;
 
 size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
 
+// Device address of `scratch` on the current device, looked up once per device with that device current.
+int static_scratch(void **out)
+{
+    static void *ptr[16] = {};
+    static std::mutex guard;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess)
+        return (int)e;
+    if (dev < 0 || dev >= 16)
+        return (int)hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(guard);
+    if (!ptr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess)
+            return (int)e;
+        if (!p)
+            return (int)hipErrorInvalidSymbol;
+        ptr[dev] = p;
+    }
+    *out = ptr[dev];
+    return 0;
+}
+
 } // namespace
 
 extern "C" int fq_dequant(const void *packed, const void *scales, const void *zeros, int N, int K, int bits,
@@ -90,7 +125,10 @@ extern "C" int fq_qlinear(const void *x, int M, const void *packed, const void *
 
 extern "C" int fq_init(void)
 {
-    return check_hip(fq_gemv_prepare(), "fq_init");
+    if (int rc = check_hip(fq_gemv_prepare(), "fq_init"))
+        return rc;
+    void *p = nullptr;
+    return check_hip(static_scratch(&p), "fq_init: static scratch");
 }
 
 extern "C" int fq_dense_f16(const void *x, int M, const void *W, int N, int K, void *out, void *stream)
@@ -233,6 +271,30 @@ extern "C" int fq_stack_forward(const fq_layer *layers, int L, const uint8_t *bi
     if (!aligned16(x_in) || !aligned16(x_out) || !aligned16(workspace))
         return fq_fail(FQ_ERR_ALIGN, "fq_stack_forward: x_in, x_out and workspace must be 16-byte aligned");
     return stack_forward_checked(layers, L, bitvec, x_in, M, x_out, workspace, H, F, static_cast<fq_stream>(stream));
+}
+
+extern "C" int fq_stack_forward_noalloc(const fq_layer *layers, int L, const uint8_t *bitvec, const void *x_in, int M,
+                                        void *x_out, void *stream)
+{
+    if (!layers || !bitvec || !x_in || !x_out)
+        return fq_fail(FQ_ERR_NULL, "fq_stack_forward_noalloc: NULL argument");
+    if (L <= 0 || M <= 0)
+        return fq_fail(FQ_ERR_SHAPE, "fq_stack_forward_noalloc: L=%d M=%d", L, M);
+    if (M > kNoallocMaxM)
+        return fq_fail(FQ_ERR_SHAPE, "fq_stack_forward_noalloc: M=%d exceeds the %d rows the library's own scratch "
+                       "holds; use fq_stack_forward with a workspace", M, kNoallocMaxM);
+    int H = 0, F = 0;
+    if (int rc = validate_layers("fq_stack_forward_noalloc", layers, L, bitvec, &H, &F))
+        return rc;
+    if (H > kNoallocMaxDim || F > kNoallocMaxDim || fq_stack_workspace_bytes(M, H, F) > kNoallocScratchBytes)
+        return fq_fail(FQ_ERR_SHAPE, "fq_stack_forward_noalloc: hidden=%d ffn=%d exceed the %d elements per row the "
+                       "library's own scratch holds; use fq_stack_forward with a workspace", H, F, kNoallocMaxDim);
+    if (!aligned16(x_in) || !aligned16(x_out))
+        return fq_fail(FQ_ERR_ALIGN, "fq_stack_forward_noalloc: x_in and x_out must be 16-byte aligned");
+    void *ws = nullptr;
+    if (int rc = check_hip(static_scratch(&ws), "fq_stack_forward_noalloc: static scratch"))
+        return rc;
+    return stack_forward_checked(layers, L, bitvec, x_in, M, x_out, ws, H, F, static_cast<fq_stream>(stream));
 }
 
 // The launches of a stack forward; every argument has been validated and the workspace holds
