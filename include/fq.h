@@ -198,6 +198,48 @@ int fq_stack_forward(const fq_layer *layers, int L, const uint8_t *bitvec,
 int fq_stack_forward_noalloc(const fq_layer *layers, int L, const uint8_t *bitvec,
                              const void *x_in, int M, void *x_out, void *stream);
 
+/*
+ * Decode path and its error reporting.  With M == 1 the stack forwards above can run
+ * the whole stack in one persistent launch per sixteen blocks (hidden <= 8192, ffn
+ * <= 16384): one workgroup per compute unit, all resident together, streaming the
+ * packed weights through LDS rings that keep loading across the block's four
+ * dependent phases, and meeting at a grid-wide barrier after each phase.
+ *   fq_set_decode_mode(1) selects that kernel for M == 1 where it applies; mode 0,
+ *     the default, runs the per-phase launches that also serve 2 <= M <= 16 (four
+ *     launches per block).  The previous mode is returned.  Process-wide.  As
+ *     measured on MI355X the per-phase launches are the faster of the two.
+ * Every wait of the persistent kernel's barrier is bounded by a timer; a workgroup
+ * that waits longer gives up, the launch still ends, its results are invalid, and
+ * from then on fq_stack_forward and fq_stack_forward_noalloc return FQ_ERR_HIP (the
+ * library does not synchronise, so the failure surfaces at the next call, as
+ * fq_async_error() does at any time) until fq_clear_async_error() is called.
+ *   fq_decode_give_up_ticks(t) sets the bound in ticks of the 100 MHz timer
+ *     (default 2 s) and returns the previous one; 0 makes every wait give up at
+ *     once, which is how the tests exercise the failure path.
+ * The no-alloc variant runs the persistent kernel only after fq_init() on that
+ * device (the preparation pins one word of host memory for the error report).
+ */
+int fq_set_decode_mode(int mode);
+/* Non-zero (the depth of a wavefront's LDS ring in KiB) if, on the current device and after fq_init(), the
+ * persistent kernel can serve M == 1 forwards through blocks of this size when mode 1 selects it; else 0. */
+int fq_decode_persistent(int hidden, int ffn);
+/* Launches of the persistent kernel this process has queued so far (tests use it to see which path ran). */
+unsigned long long fq_decode_persistent_launches(void);
+unsigned long long fq_decode_give_up_ticks(unsigned long long ticks);
+/*
+ * How the persistent kernel deals a phase's work to its workgroups (host; for tests
+ * and tools).  Phase 0..3 = q/k/v, o, gate/up, down of a block whose seven matrices
+ * have the bit-widths bits7 (host, 7 entries); N = rows of the phase's matrices.  A
+ * work unit is a supertile row (32/64/16/16 weight rows at 2/3/4/8 bits); every
+ * matrix of the phase is cut into `grid` contiguous runs of nearly equal length,
+ * the odd matrices dealt in reverse workgroup order.  units_out (host, 6 ints)
+ * receives [first, end) of workgroup wg's units in each of the phase's (up to
+ * three) matrices; unused pairs are 0, 0.
+ */
+int fq_decode_partition(const uint8_t *bits7, int phase, int N, int wg, int grid, int *units_out);
+int fq_async_error(void);
+void fq_clear_async_error(void);
+
 /* Single glue steps of the block above, exposed for layer-by-layer parity checks.
  * All tensors fp16 [M,H] row-major on the device; b and c may be NULL where unused.
  *   op 0: out = rms(a)              op 1: out = rms(a + b + c)

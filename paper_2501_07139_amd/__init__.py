@@ -61,6 +61,13 @@ def _load() -> ctypes.CDLL:
         "fq_stack_workspace_bytes": (sz, [ci, ci, ci]),
         "fq_stack_forward": (ci, [ctypes.POINTER(fq_layer), ci, vp, vp, ci, vp, vp, sz, vp]),
         "fq_stack_forward_noalloc": (ci, [ctypes.POINTER(fq_layer), ci, vp, vp, ci, vp, vp]),
+        "fq_set_decode_mode": (ci, [ci]),
+        "fq_decode_give_up_ticks": (ctypes.c_ulonglong, [ctypes.c_ulonglong]),
+        "fq_async_error": (ci, []),
+        "fq_decode_persistent": (ci, [ci, ci]),
+        "fq_decode_persistent_launches": (ctypes.c_ulonglong, []),
+        "fq_decode_partition": (ci, [vp, ci, ci, ci, ci, vp]),
+        "fq_clear_async_error": (None, []),
         "fq_glue": (ci, [ci, vp, vp, vp, ci, ci, vp, vp]),
         "fq_init": (ci, []),
         "fq_dense_f16": (ci, [vp, ci, vp, ci, ci, vp, vp]),
@@ -92,7 +99,9 @@ EXPORTS = ("fq_last_error", "fq_version", "fq_quantize_rtn", "fq_packed_bytes", 
            "fq_token_nll", "fq_logit_l2", "fq_head_nll_workspace_bytes", "fq_head_nll",
            "fq_attn_workspace_bytes", "fq_decode_workspace_bytes", "fq_attn_decode", "fq_decode_step",
            "fq_attn_prefill_workspace_bytes", "fq_prefill_workspace_bytes", "fq_attn_prefill", "fq_prefill_forward",
-           "fq_init", "fq_dense_f16_tile", "fq_rope_table", "fq_stack_forward_noalloc")
+           "fq_init", "fq_dense_f16_tile", "fq_rope_table", "fq_stack_forward_noalloc", "fq_set_decode_mode",
+           "fq_decode_give_up_ticks", "fq_async_error", "fq_clear_async_error", "fq_decode_partition", "fq_decode_persistent",
+           "fq_decode_persistent_launches")
 
 
 def _check(rc: int) -> None:
@@ -272,6 +281,39 @@ def fq_stack_forward(stack: Stack, bitvec, x, out=None, workspace=None, stream=N
     _check(_lib.fq_stack_forward(stack.table, stack.L, _hp(bitvec), _dp(x), M, _dp(out), _dp(workspace),
                                  workspace.numel(), _stream(stream)))
     return out
+
+
+def fq_set_decode_mode(mode: int) -> int:
+    """0: per-phase launches (default); 1: the persistent kernel for M == 1 where it applies.  Returns the previous mode."""
+    return _lib.fq_set_decode_mode(mode)
+
+
+def fq_decode_give_up_ticks(ticks: int) -> int:
+    return _lib.fq_decode_give_up_ticks(ticks)
+
+
+def fq_decode_partition(bits7, phase: int, N: int, wg: int, grid: int):
+    """[(first, end)] of workgroup wg's work units in each matrix of the phase (see fq.h)."""
+    bits7 = _np(np.asarray(bits7, dtype=np.uint8), np.uint8)
+    out = np.zeros(6, dtype=np.int32)
+    _check(_lib.fq_decode_partition(_hp(bits7), phase, N, wg, grid, _hp(out)))
+    return [(int(out[2 * j]), int(out[2 * j + 1])) for j in range(3)]
+
+
+def fq_decode_persistent(hidden: int, ffn: int) -> int:
+    return _lib.fq_decode_persistent(hidden, ffn)
+
+
+def fq_decode_persistent_launches() -> int:
+    return _lib.fq_decode_persistent_launches()
+
+
+def fq_async_error() -> int:
+    return _lib.fq_async_error()
+
+
+def fq_clear_async_error() -> None:
+    _lib.fq_clear_async_error()
 
 
 def fq_stack_forward_noalloc(stack: Stack, bitvec, x, out, stream=None):

@@ -22,7 +22,7 @@ CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libfq.so")
 
-SOURCES = ["fq_host.cpp", "fq_api.hip", "fq_gemv.hip", "fq_gemm.hip", "fq_dense.hip", "fq_attn.hip", "fq_rowops.hip"]
+SOURCES = ["fq_host.cpp", "fq_api.hip", "fq_gemv.hip", "fq_decode.hip", "fq_gemm.hip", "fq_dense.hip", "fq_attn.hip", "fq_rowops.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-function",

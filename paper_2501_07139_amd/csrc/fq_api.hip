@@ -14,7 +14,7 @@
 // copy of this array until the process ends.  In host code the array's name is only a handle: the device
 // address comes from hipGetSymbolAddress (static_scratch below) and is what kernels and copies are given.
 constexpr int kNoallocMaxM = 16, kNoallocMaxDim = 16384;
-constexpr size_t kNoallocScratchBytes = (size_t)13 * kNoallocMaxM * kNoallocMaxDim * 2;
+constexpr size_t kNoallocScratchBytes = (size_t)13 * kNoallocMaxM * kNoallocMaxDim * 2 + fq_decode_sync_bytes;
 static __device__ __align__(256) unsigned char scratch[kNoallocScratchBytes];
 
 namespace {
@@ -126,6 +126,8 @@ extern "C" int fq_qlinear(const void *x, int M, const void *packed, const void *
 extern "C" int fq_init(void)
 {
     if (int rc = check_hip(fq_gemv_prepare(), "fq_init"))
+        return rc;
+    if (int rc = check_hip(fq_decode_prepare(), "fq_init: decode kernel"))
         return rc;
     void *p = nullptr;
     return check_hip(static_scratch(&p), "fq_init: static scratch");
@@ -243,17 +245,44 @@ static int validate_layers(const char *fn, const fq_layer *layers, int L, const 
     return FQ_OK;
 }
 
-// Workspace: u, q, k, v, a, o, x1, u2, d, xcur (hidden wide) and g, p, m (ffn wide).
+// Workspace: u, q, k, v, a, o, x1, u2, d, xcur (hidden wide), g, p, m (ffn wide), then the counters of the
+// persistent decode kernel's grid barrier.
 extern "C" size_t fq_stack_workspace_bytes(int M, int hidden, int ffn)
 {
     if (M <= 0 || hidden <= 0 || ffn <= 0)
         return 0;
     const size_t h = align_up((size_t)M * hidden * 2), f = align_up((size_t)M * ffn * 2);
-    return 10 * h + 3 * f;
+    return 10 * h + 3 * f + fq_decode_sync_bytes;
+}
+
+static const char kGaveUp[] = "an earlier decode kernel gave up waiting at its grid barrier (its results are invalid); "
+                              "fq_clear_async_error() re-arms the library";
+
+extern "C" int fq_set_decode_mode(int mode) { return fq_decode_set_mode(mode); }
+extern "C" unsigned long long fq_decode_give_up_ticks(unsigned long long ticks) { return fq_decode_set_give_up_ticks(ticks); }
+extern "C" int fq_decode_persistent(int hidden, int ffn) { return fq_decode_available(hidden, ffn); }
+extern "C" unsigned long long fq_decode_persistent_launches(void) { return fq_decode_launches(); }
+extern "C" int fq_async_error(void) { return fq_decode_async_error() ? FQ_ERR_HIP : FQ_OK; }
+extern "C" void fq_clear_async_error(void) { fq_decode_clear_async_error(); }
+
+extern "C" int fq_decode_partition(const uint8_t *bits7, int phase, int N, int wg, int grid, int *units_out)
+{
+    if (!bits7 || !units_out)
+        return fq_fail(FQ_ERR_NULL, "fq_decode_partition: NULL argument");
+    if (phase < 0 || phase > 3 || N <= 0 || grid <= 0 || wg < 0 || wg >= grid)
+        return fq_fail(FQ_ERR_SHAPE, "fq_decode_partition: phase=%d N=%d wg=%d grid=%d", phase, N, wg, grid);
+    unsigned bits4 = 0;
+    for (int j = 0; j < 7; ++j) {
+        if (fq_bits_index(bits7[j]) < 0)
+            return fq_fail(FQ_ERR_BITS, "fq_decode_partition: bits=%d not in {2,3,4,8}", (int)bits7[j]);
+        bits4 |= (unsigned)bits7[j] << (4 * j);
+    }
+    fq_decode_partition_of(bits4, phase, N, wg, grid, units_out);
+    return FQ_OK;
 }
 
 static int stack_forward_checked(const fq_layer *layers, int L, const uint8_t *bitvec, const void *x_in, int M,
-                                 void *x_out, void *workspace, int H, int F, fq_stream st);
+                                 void *x_out, void *workspace, int H, int F, bool may_allocate, fq_stream st);
 
 extern "C" int fq_stack_forward(const fq_layer *layers, int L, const uint8_t *bitvec, const void *x_in, int M,
                                 void *x_out, void *workspace, size_t workspace_bytes, void *stream)
@@ -270,7 +299,9 @@ extern "C" int fq_stack_forward(const fq_layer *layers, int L, const uint8_t *bi
                        fq_stack_workspace_bytes(M, H, F));
     if (!aligned16(x_in) || !aligned16(x_out) || !aligned16(workspace))
         return fq_fail(FQ_ERR_ALIGN, "fq_stack_forward: x_in, x_out and workspace must be 16-byte aligned");
-    return stack_forward_checked(layers, L, bitvec, x_in, M, x_out, workspace, H, F, static_cast<fq_stream>(stream));
+    if (fq_decode_async_error())
+        return fq_fail(FQ_ERR_HIP, "fq_stack_forward: %s", kGaveUp);
+    return stack_forward_checked(layers, L, bitvec, x_in, M, x_out, workspace, H, F, true, static_cast<fq_stream>(stream));
 }
 
 extern "C" int fq_stack_forward_noalloc(const fq_layer *layers, int L, const uint8_t *bitvec, const void *x_in, int M,
@@ -294,13 +325,15 @@ extern "C" int fq_stack_forward_noalloc(const fq_layer *layers, int L, const uin
     void *ws = nullptr;
     if (int rc = check_hip(static_scratch(&ws), "fq_stack_forward_noalloc: static scratch"))
         return rc;
-    return stack_forward_checked(layers, L, bitvec, x_in, M, x_out, ws, H, F, static_cast<fq_stream>(stream));
+    if (fq_decode_async_error())
+        return fq_fail(FQ_ERR_HIP, "fq_stack_forward_noalloc: %s", kGaveUp);
+    return stack_forward_checked(layers, L, bitvec, x_in, M, x_out, ws, H, F, false, static_cast<fq_stream>(stream));
 }
 
 // The launches of a stack forward; every argument has been validated and the workspace holds
 // fq_stack_workspace_bytes(M, H, F) bytes.
 static int stack_forward_checked(const fq_layer *layers, int L, const uint8_t *bitvec, const void *x_in, int M,
-                                 void *x_out, void *workspace, int H, int F, fq_stream st)
+                                 void *x_out, void *workspace, int H, int F, bool may_allocate, fq_stream st)
 {
     fq_packed_ref sel[7];
     const size_t hb = align_up((size_t)M * H * 2), fb = align_up((size_t)M * F * 2);
@@ -308,6 +341,16 @@ static int stack_forward_checked(const fq_layer *layers, int L, const uint8_t *b
     void *u = ws, *q = ws + hb, *k = ws + 2 * hb, *v = ws + 3 * hb, *a = ws + 4 * hb, *o = ws + 5 * hb,
          *x1 = ws + 6 * hb, *u2 = ws + 7 * hb, *d = ws + 8 * hb, *xc = ws + 9 * hb;
     void *g = ws + 10 * hb, *p = ws + 10 * hb + fb, *mm = ws + 10 * hb + 2 * fb;
+
+    // One token: the whole stack in one persistent launch where that kernel applies.
+    if (M == 1) {
+        const fq_decode_buffers bufs = {q, k, v, o, g, p, d, x1, ws + 10 * hb + 3 * fb};
+        const int e = fq_launch_decode_persist(layers, L, bitvec, H, F, x_in, x_out, bufs, may_allocate, st);
+        if (e == 0)
+            return FQ_OK;
+        if (e > 0)
+            return check_hip(e, "decode (persistent kernel)");
+    }
 
     // Decode (M <= 16): four launches per block.  q/k/v and gate/up share a launch each, and every
     // row-wise step is folded into the input staging of the linear that consumes it.

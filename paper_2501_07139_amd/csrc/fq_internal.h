@@ -5,6 +5,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include "fq.h"
+
 int fq_fail(int code, const char *fmt, ...) __attribute__((format(printf, 2, 3)));
 int fq_bits_index(int bits);         // 2,3,4,8 -> 0..3, else -1
 int fq_rows_per_supertile(int bits); // 32,64,16,16
@@ -38,6 +40,25 @@ bool fq_gemv_can_stream(int M, int K, int bits, int inputs);
 int fq_gemv_prepare();
 int fq_launch_gemv_multi(const fq_gemv_input &src, int M, const fq_packed_ref *w, void *const *outs, int count,
                          fq_stream st);
+// Persistent decode kernel (M = 1): the whole stack in one launch per sixteen blocks.  Buffers are fp16
+// vectors in the caller's workspace (q, k, v, o, d, x1 hidden wide; g, p ffn wide) and 4 KiB for the
+// barrier counters.  fq_launch_decode_persist returns 0 once queued, -1 when the kernel does not apply (the
+// caller queues the per-phase launches instead), else a hipError_t.  Without may_allocate nothing is set up
+// on a device that fq_decode_prepare has not seen (the preparation pins a word of host memory).
+struct fq_decode_buffers {
+    void *q, *k, *v, *o, *g, *p, *d, *x1, *sync;
+};
+constexpr size_t fq_decode_sync_bytes = 4096;
+int fq_decode_prepare();
+int fq_launch_decode_persist(const fq_layer *layers, int L, const uint8_t *bitvec, int H, int F, const void *x_in,
+                             void *x_out, const fq_decode_buffers &b, bool may_allocate, fq_stream st);
+bool fq_decode_async_error();        // a decode kernel has given up at its grid barrier on this device
+void fq_decode_clear_async_error();
+unsigned long long fq_decode_set_give_up_ticks(unsigned long long ticks); // returns the previous bound
+int fq_decode_set_mode(int mode);    // 0: per-phase launches (default), 1: persistent kernel where it applies; returns the previous
+unsigned long long fq_decode_launches(); // persistent launches queued by this process so far
+int fq_decode_available(int H, int F); // pages per ring if the persistent kernel would run, else 0
+void fq_decode_partition_of(unsigned bits4, int ph, int N, int wg, int grid, int *out6);    // 0: persistent kernel where it applies, 1: per-phase launches; returns the previous
 int fq_launch_gemm(const void *x, int M, const fq_packed_ref &w, void *out, fq_stream st);
 // Up to three matrices with the same input (same K) in one launch, M > 16.
 int fq_launch_gemm_multi(const void *x, int M, const fq_packed_ref *w, void *const *outs, int count, fq_stream st);
