@@ -143,10 +143,18 @@ int fq_dequant(const void *packed, const void *scales, const void *zeros,
  * N >= 1.  Scales and zeros may be any finite fp16 (e.g. zero/2^d after
  * truncating d code bits, Section "Elastic Serving").  For M > 16 the
  * activations (M*K*2 bytes) and the packed weights must each stay below
- * 4 GiB, else FQ_ERR_SHAPE.
+ * 4 GiB, else FQ_ERR_SHAPE.  Two tile kernels exist for M > 16: 128 activation
+ * rows per workgroup (the library's choice: the faster one as measured), and 256
+ * rows with K split over two wavefront pairs (each unpacked weight feeds twice as
+ * many matrix instructions).  fq_qlinear_tile is the same call with the choice
+ * made by the caller: tile_rows = 128 or 256 pins a kernel (any M > 16; for tests
+ * and tuning; ignored for M <= 16), 0 leaves it to the library; anything else is
+ * FQ_ERR_SHAPE.
  */
 int fq_qlinear(const void *x, int M, const void *packed, const void *scales, const void *zeros,
                int N, int K, int bits, int group, void *out, void *stream);
+int fq_qlinear_tile(const void *x, int M, const void *packed, const void *scales, const void *zeros,
+                    int N, int K, int bits, int group, void *out, int tile_rows, void *stream);
 
 /* One matrix in all stored bit-widths; index 0..3 = bits 2, 3, 4, 8.  Unused widths may be NULL. */
 typedef struct {

@@ -58,6 +58,7 @@ def _load() -> ctypes.CDLL:
         "fq_pack_groups": (ci, [vp, vp, vp, ci, ci, ci, ci, vp, vp, vp]),
         "fq_dequant": (ci, [vp, vp, vp, ci, ci, ci, ci, vp, ci, vp]),
         "fq_qlinear": (ci, [vp, ci, vp, vp, vp, ci, ci, ci, ci, vp, vp]),
+        "fq_qlinear_tile": (ci, [vp, ci, vp, vp, vp, ci, ci, ci, ci, vp, ci, vp]),
         "fq_stack_workspace_bytes": (sz, [ci, ci, ci]),
         "fq_stack_forward": (ci, [ctypes.POINTER(fq_layer), ci, vp, vp, ci, vp, vp, sz, vp]),
         "fq_stack_forward_noalloc": (ci, [ctypes.POINTER(fq_layer), ci, vp, vp, ci, vp, vp]),
@@ -95,7 +96,7 @@ def _load() -> ctypes.CDLL:
 
 _lib = _load()
 EXPORTS = ("fq_last_error", "fq_version", "fq_quantize_rtn", "fq_packed_bytes", "fq_meta_count", "fq_pack_groups",
-           "fq_dequant", "fq_qlinear", "fq_stack_workspace_bytes", "fq_stack_forward", "fq_glue", "fq_dense_f16",
+           "fq_dequant", "fq_qlinear", "fq_qlinear_tile", "fq_stack_workspace_bytes", "fq_stack_forward", "fq_glue", "fq_dense_f16",
            "fq_token_nll", "fq_logit_l2", "fq_head_nll_workspace_bytes", "fq_head_nll",
            "fq_attn_workspace_bytes", "fq_decode_workspace_bytes", "fq_attn_decode", "fq_decode_step",
            "fq_attn_prefill_workspace_bytes", "fq_prefill_workspace_bytes", "fq_attn_prefill", "fq_prefill_forward",
@@ -225,7 +226,7 @@ def fq_dequant(w: PackedMatrix, fp16: bool = False, stream=None):
     return out
 
 
-def fq_qlinear(x, w: PackedMatrix, out=None, stream=None, group: int = GROUP):
+def fq_qlinear(x, w: PackedMatrix, out=None, stream=None, group: int = GROUP, tile_rows: int = 0):
     torch = _torch()
     x = _dev(x, torch.float16, "x")
     M, K = x.shape
@@ -234,8 +235,8 @@ def fq_qlinear(x, w: PackedMatrix, out=None, stream=None, group: int = GROUP):
     if out is None:
         out = torch.empty((M, w.N), dtype=torch.float16, device=x.device)
     _dev(out, torch.float16, "out")
-    _check(_lib.fq_qlinear(_dp(x), M, _dp(w.packed), _dp(w.scales), _dp(w.zeros), w.N, w.K, w.bits, group, _dp(out),
-                           _stream(stream)))
+    _check(_lib.fq_qlinear_tile(_dp(x), M, _dp(w.packed), _dp(w.scales), _dp(w.zeros), w.N, w.K, w.bits, group,
+                                _dp(out), tile_rows, _stream(stream)))
     return out
 
 

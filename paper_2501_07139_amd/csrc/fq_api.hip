@@ -47,12 +47,12 @@ int check_matrix(const char *fn, const void *packed, const void *scales, const v
 // The M > 16 kernels address each array through 32-bit byte offsets.
 bool below_4gib(size_t a, size_t b, size_t elem_bytes) { return a * b * elem_bytes < ((size_t)1 << 32); }
 
-int qlinear_checked(const void *x, int M, const fq_packed_ref &w, void *out, fq_stream st)
+int qlinear_checked(const void *x, int M, const fq_packed_ref &w, void *out, fq_stream st, int tile_rows = 0)
 {
     if (M > 16 && (!below_4gib(M, w.K, 2) || !below_4gib(((size_t)w.N + 63) / 64 * 8, w.K, w.bits)))
         return fq_fail(FQ_ERR_SHAPE, "fq_qlinear: M=%d N=%d K=%d: activations and packed weights must each stay "
                        "below 4 GiB", M, w.N, w.K);
-    int e = (M <= 16) ? fq_launch_gemv(x, M, w, out, st) : fq_launch_gemm(x, M, w, out, st);
+    int e = (M <= 16) ? fq_launch_gemv(x, M, w, out, st) : fq_launch_gemm(x, M, w, out, st, tile_rows);
     return check_hip(e, "fq_qlinear launch");
 }
 
@@ -111,6 +111,14 @@ extern "C" int fq_dequant(const void *packed, const void *scales, const void *ze
 extern "C" int fq_qlinear(const void *x, int M, const void *packed, const void *scales, const void *zeros,
                           int N, int K, int bits, int group, void *out, void *stream)
 {
+    return fq_qlinear_tile(x, M, packed, scales, zeros, N, K, bits, group, out, 0, stream);
+}
+
+extern "C" int fq_qlinear_tile(const void *x, int M, const void *packed, const void *scales, const void *zeros,
+                               int N, int K, int bits, int group, void *out, int tile_rows, void *stream)
+{
+    if (tile_rows != 0 && tile_rows != 128 && tile_rows != 256)
+        return fq_fail(FQ_ERR_SHAPE, "fq_qlinear_tile: tile_rows=%d (0, 128 or 256)", tile_rows);
     if (int rc = check_matrix("fq_qlinear", packed, scales, zeros, N, K, bits, group))
         return rc;
     if (!x || !out)
@@ -120,7 +128,7 @@ extern "C" int fq_qlinear(const void *x, int M, const void *packed, const void *
     if (!aligned16(x) || !aligned16(out))
         return fq_fail(FQ_ERR_ALIGN, "fq_qlinear: x and out must be 16-byte aligned");
     fq_packed_ref w{packed, scales, zeros, N, K, bits};
-    return qlinear_checked(x, M, w, out, static_cast<fq_stream>(stream));
+    return qlinear_checked(x, M, w, out, static_cast<fq_stream>(stream), tile_rows);
 }
 
 extern "C" int fq_init(void)

@@ -58,10 +58,12 @@ unsigned long long fq_decode_set_give_up_ticks(unsigned long long ticks); // ret
 int fq_decode_set_mode(int mode);    // 0: per-phase launches (default), 1: persistent kernel where it applies; returns the previous
 unsigned long long fq_decode_launches(); // persistent launches queued by this process so far
 int fq_decode_available(int H, int F); // pages per ring if the persistent kernel would run, else 0
-void fq_decode_partition_of(unsigned bits4, int ph, int N, int wg, int grid, int *out6);    // 0: persistent kernel where it applies, 1: per-phase launches; returns the previous
-int fq_launch_gemm(const void *x, int M, const fq_packed_ref &w, void *out, fq_stream st);
+void fq_decode_partition_of(unsigned bits4, int ph, int N, int wg, int grid, int *out6);
+// M > 16.  tile_rows: 0 lets the library choose between the 128-row and the 256-row tile kernels, 128 or 256 pins one.
+int fq_launch_gemm(const void *x, int M, const fq_packed_ref &w, void *out, fq_stream st, int tile_rows = 0);
 // Up to three matrices with the same input (same K) in one launch, M > 16.
-int fq_launch_gemm_multi(const void *x, int M, const fq_packed_ref *w, void *const *outs, int count, fq_stream st);
+int fq_launch_gemm_multi(const void *x, int M, const fq_packed_ref *w, void *const *outs, int count, fq_stream st,
+                         int tile_rows = 0);
 int fq_launch_dense(const void *x, int M, const void *W, int N, int K, void *out, fq_stream st);
 // The same product with 256 x 256 tiles, both operands through LDS; pays once its tiles fill the chip.
 bool fq_dense_tiled_pays(int M, int N);

@@ -86,6 +86,29 @@ def test_dequant_arbitrary_codes_and_fractional_zeros(fq, torch, bits):
     assert np.array_equal(got.view(np.uint32), oracle.dequant(codes, s, z).view(np.uint32))
 
 
+class Guarded:
+    """A device buffer of `nbytes` with 4 KiB of a known pattern on either side."""
+    PAD = 4096
+
+    def __init__(self, torch, nbytes, fill=0xA5):
+        self.torch, self.n = torch, nbytes
+        self.raw = torch.full((nbytes + 2 * self.PAD,), fill, dtype=torch.uint8, device="cuda")
+        self.fill = fill
+
+    def bytes(self):
+        return self.raw[self.PAD:self.PAD + self.n]
+
+    def half(self, *shape):
+        return self.bytes().view(self.torch.float16).view(*shape)
+
+    def f32(self, *shape):
+        return self.bytes().view(self.torch.float32).view(*shape)
+
+    def intact(self):
+        lo, hi = self.raw[:self.PAD], self.raw[self.PAD + self.n:]
+        return bool((lo == self.fill).all().item()) and bool((hi == self.fill).all().item())
+
+
 # ------------------------------------------------------------------- qlinear
 GEMV_CASES = [(1, 512, 512), (16, 512, 512), (3, 200, 384), (1, 4096, 4096), (5, 70, 256), (1, 1, 128),
               (1, 160, 11008), (3, 96, 11008)]  # rows longer than one pass of the staging
@@ -104,6 +127,36 @@ def test_qlinear_against_oracle(fq, torch, bits, case):
     assert qerr(y, r) <= TOL
     # plain max-norm figure as well, for the record
     assert np.max(np.abs(y.astype(np.float64) - r)) / np.max(np.abs(r)) <= TOL
+
+
+# 256-row tiles (two halves of K per workgroup): one group, odd and even group counts, ragged rows and columns,
+# rows that leave the last tile almost empty
+TALL_CASES = [(256, 128, 128), (300, 200, 384), (520, 384, 1024), (17, 70, 256), (512, 1030, 640), (700, 264, 2816)]
+
+
+@pytest.mark.parametrize("bits", BITS)
+@pytest.mark.parametrize("case", TALL_CASES, ids=lambda c: "M%d_N%d_K%d" % c)
+def test_qlinear_tall_tiles_against_oracle(fq, torch, bits, case):
+    M, N, K = case
+    w, codes, s, z = make_matrix(fq, 120 + bits, N, K, bits)
+    X = fq_synth.activations(11, M, K)
+    r = oracle.qlinear(X, oracle.dequant(codes, s, z))
+    out = Guarded(torch, M * N * 2)
+    fq.fq_qlinear(dev(torch, X), w, out=out.half(M, N), tile_rows=256)
+    torch.cuda.synchronize()
+    assert out.intact()
+    y = host16(out.half(M, N))
+    assert qerr(y, r) <= TOL
+    # the 128-row kernel on the same inputs: same products, fp32 sums in another order
+    y128 = host16(fq.fq_qlinear(dev(torch, X), w, tile_rows=128))
+    assert qerr(y, y128.astype(np.float64)) <= 1e-3
+
+
+def test_qlinear_tile_rejects_other_tile_heights(fq, torch):
+    w, *_ = make_matrix(fq, 1, 64, 128, 4)
+    with pytest.raises(fq.FqError) as e:
+        fq.fq_qlinear(dev(torch, fq_synth.activations(1, 32, 128)), w, tile_rows=64)
+    assert e.value.code == -2
 
 
 @pytest.mark.parametrize("bits", BITS)
@@ -575,10 +628,11 @@ def test_gemm_unpack_is_bit_exact_through_an_identity(fq, torch, bits, shape, fr
     N, K = shape
     w, W32 = _random_packing(fq, 900 + bits, N, K, bits, fractional)
     X = np.eye(K, dtype=np.float16)
-    y = host16(fq.fq_qlinear(dev(torch, X), w))
-    want = oracle.round_f16(W32.astype(np.float64)).T
-    assert y.shape == want.shape
-    assert np.array_equal(y.view(np.uint16), np.ascontiguousarray(want).view(np.uint16))
+    want = np.ascontiguousarray(oracle.round_f16(W32.astype(np.float64)).T)
+    for tile_rows in (128, 256, 0):   # either tile kernel, and the library's own choice
+        y = host16(fq.fq_qlinear(dev(torch, X), w, tile_rows=tile_rows))
+        assert y.shape == want.shape
+        assert np.array_equal(y.view(np.uint16), want.view(np.uint16)), tile_rows
 
 
 @pytest.mark.parametrize("fractional", [False, True], ids=["int_zero", "frac_zero"])
@@ -639,29 +693,6 @@ def test_quantize_pack_qlinear_from_the_librarys_own_quantizer(fq, torch, bits):
 
 
 # ---------------------------------------------- guard bytes around every buffer
-class Guarded:
-    """A device buffer of `nbytes` with 4 KiB of a known pattern on either side."""
-    PAD = 4096
-
-    def __init__(self, torch, nbytes, fill=0xA5):
-        self.torch, self.n = torch, nbytes
-        self.raw = torch.full((nbytes + 2 * self.PAD,), fill, dtype=torch.uint8, device="cuda")
-        self.fill = fill
-
-    def bytes(self):
-        return self.raw[self.PAD:self.PAD + self.n]
-
-    def half(self, *shape):
-        return self.bytes().view(self.torch.float16).view(*shape)
-
-    def f32(self, *shape):
-        return self.bytes().view(self.torch.float32).view(*shape)
-
-    def intact(self):
-        lo, hi = self.raw[:self.PAD], self.raw[self.PAD + self.n:]
-        return bool((lo == self.fill).all().item()) and bool((hi == self.fill).all().item())
-
-
 @pytest.mark.parametrize("bits", BITS)
 @pytest.mark.parametrize("case", [(1, 70, 256), (5, 200, 384), (16, 96, 11008), (33, 70, 256), (300, 200, 384),
                                   (129, 1030, 512)], ids=lambda c: "M%d_N%d_K%d" % c)
