@@ -12,8 +12,14 @@ synthetic activations.  One step is one pass of the whole path:
         distinct copies of the block, so that every pass streams more packed bytes
         than the 256 MB last-level cache holds (cold weights, launch gaps included).
 
-Prints ONE JSON line.  `value` is the algorithmic TFLOP/s of the whole step;
-`legs` breaks it down (GEMM TFLOP/s at M=2048, GEMV GB/s at M=1, NLL GB/s);
+Prints ONE JSON line.  `value` is the dequant-GEMM rate at M=2048 (algorithmic flops of
+the block's seven launches over the sum of their median durations); the decode rate
+(packed bytes per second over the cold 8-block stack) is in `roofline_gemv`; `legs`
+holds the step's other parts and the legs beyond the step: the 13B-shaped block at
+M=4096 and M=1, the ensemble sweep (64 bit vectors x 4 sequences over a 32-block
+stack), single decode launches rotating over more than 512 MB, a plain streaming
+read of the decode footprint as the practical ceiling.  Kernel durations are taken
+with events on the launch stream, 50 repetitions, median and minimum reported.
 `roofline` is for the kernel the step spends most of its time in (the dequant-GEMM);
 `cpu_baseline` times the CPU oracle on a bounded sample of the same workload.
 """
@@ -34,6 +40,10 @@ import numpy as np  # noqa: E402
 HIDDEN, FFN, VOCAB = 4096, 11008, 32000
 M_FWD = 2048
 DECODE_LAYERS = 8
+REPS = 50                      # repetitions behind every median / minimum
+ROTATE_BYTES = 512 << 20       # single decode launches rotate over at least this much packed data
+HIDDEN_13B, FFN_13B, M_13B = 5120, 13824, 4096
+SWEEP_VECTORS, SWEEP_SEQUENCES = 64, 4
 PEAK_MFMA_F16_TFLOPS = 2516.6  # 256 CU x 4096 flop/clk x 2.4 GHz
 PEAK_HBM_GBPS = 8000.0
 SEED = 1
@@ -85,6 +95,7 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     dev = torch.device("cuda:0")
+    fq.fq_init()  # kernel attributes and occupancy figures, once: every later call only enqueues work
 
     def to_dev(a):
         if a.dtype == np.float16:
@@ -184,25 +195,34 @@ def main():
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
 
-    # per-leg and per-kernel durations with events on the launch stream
-    def timed(fn, reps):
+    # per-leg and per-kernel durations with events on the launch stream: one pair of events per repetition,
+    # all queued before the first wait, so the device never idles between them
+    def durations(fn, reps=REPS):
+        fn()
         torch.cuda.synchronize()
-        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        a.record()
-        for _ in range(reps):
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+        for a, b in ev:
+            a.record()
             fn()
-        b.record()
+            b.record()
         torch.cuda.synchronize()
-        return a.elapsed_time(b) / reps  # ms
+        return np.array([a.elapsed_time(b) for a, b in ev])  # ms
 
-    reps = max(5, args.steps)
+    def timed(fn, reps=REPS):
+        return float(np.median(durations(fn, reps)))
+
+    def med_min(fn, reps=REPS, per=1):
+        d = durations(fn, reps) / per
+        return float(np.median(d)), float(d.min())
+
+    reps = REPS
     ms_fwd_block = timed(lambda: fq.fq_stack_forward(stack_fwd, bitvec, x_fwd, out=h_out, workspace=ws_fwd), reps)
     ms_head_nll = timed(lambda: fq.fq_head_nll(h_out, head, labels, out=nll, workspace=ws_head), reps)
     # the same two steps as separate calls (not part of the step): head GEMM storing its logits, loss reading them
     nll_two = torch.empty_like(nll)
     ms_head = timed(lambda: fq.fq_dense_f16(h_out, head, out=logits), reps)
     ms_nll = timed(lambda: fq.fq_token_nll(logits, labels, out=nll_two), reps)
-    ms_dec = timed(leg_b, reps)
+    ms_dec, ms_dec_min = med_min(leg_b)
     # beyond the step: the logit distance of the search's sensitivity analysis (reads two logit arrays once)
     logits_b = torch.empty_like(logits).normal_(0.0, 1.28)
     l2 = torch.empty(M_FWD, dtype=torch.float32, device=dev)
@@ -217,10 +237,10 @@ def main():
         w = block[j][int(bitvec[j])]
         xin = mm if K == FFN else u
         out = torch.empty((M_FWD, N), dtype=torch.float16, device=dev)
-        ms = timed(lambda: fq.fq_qlinear(xin, w, out=out), reps)
+        ms, ms_min = med_min(lambda: fq.fq_qlinear(xin, w, out=out))
         gemm_ms_total += ms
         kernels.append({"matrix": fq_synth.MATRIX_NAMES[j], "N": N, "K": K, "bits": int(bitvec[j]),
-                        "ms": round(ms, 4), "tflops": round(2.0 * M_FWD * N * K / ms / 1e9, 1)})
+                        "ms": round(ms, 4), "ms_min": round(ms_min, 4), "tflops": round(2.0 * M_FWD * N * K / ms / 1e9, 1)})
     gemm_tflops = gemm_flops / gemm_ms_total / 1e9
 
     # GEMV kernels of leg B, rotating over the distinct copies (cold).  The launches are replayed from a
@@ -228,7 +248,10 @@ def main():
     gemv_ms_total = 0.0
     gemv_kernels = []
     for j, (N, K) in enumerate(shapes):
-        ws = [dec_layers[l][j][int(bitvec[j])] for l in range(DECODE_LAYERS)]
+        w0 = block[j][int(bitvec[j])]
+        copies = -(-ROTATE_BYTES // w0.nbytes)  # enough distinct copies to pass 512 MB, twice the last-level cache
+        ws = [w0] + [fq.PackedMatrix(w0.packed.clone(), w0.scales.clone(), w0.zeros.clone(), w0.N, w0.K, w0.bits)
+                     for _ in range(copies - 1)]
         xin = torch.empty((1, K), dtype=torch.float16, device=dev).normal_()
         out = torch.empty((1, N), dtype=torch.float16, device=dev)
 
@@ -236,16 +259,18 @@ def main():
             for w in ws:
                 fq.fq_qlinear(xin, w, out=out)
 
-        rot()  # first use sets the kernels' attributes: not capturable
+        rot()
         torch.cuda.synchronize()
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph):
             rot()
-        ms = timed(graph.replay, reps) / DECODE_LAYERS
+        ms, ms_min = med_min(graph.replay, per=copies)
         gemv_ms_total += ms
-        nbytes = ws[0].nbytes + 2 * K + 2 * N
-        gemv_kernels.append({"matrix": fq_synth.MATRIX_NAMES[j], "N": N, "K": K, "bits": int(bitvec[j]),
-                             "us": round(ms * 1e3, 2), "GBps": round(nbytes / ms / 1e6, 1)})
+        nbytes = w0.nbytes + 2 * K + 2 * N
+        gemv_kernels.append({"matrix": fq_synth.MATRIX_NAMES[j], "N": N, "K": K, "bits": int(bitvec[j]), "copies": copies,
+                             "us": round(ms * 1e3, 2), "us_min": round(ms_min * 1e3, 2),
+                             "GBps": round(nbytes / ms / 1e6, 1)})
+        del ws, graph
 
     # ---------------------------------------------------------- legs beyond the step
     # Each runs on its own and reports {"error": ...} if it fails: the step's figures above do not depend on them.
@@ -361,10 +386,11 @@ def main():
         return big
 
     def leg_full_stack():
-        """The whole 32-block 7B-shaped stack with all four widths of every matrix resident (random packed
-        bytes, constant scales and zeros: no quantizer run), scored for a few seeded bit vectors averaging
-        about 3.5 bits: one calibration sequence of 2048 tokens through the stack, the head and the loss."""
-        L_FULL, CANDS = 32, 6
+        """The ensemble sweep: the whole 32-block 7B-shaped stack with all four widths of every matrix resident
+        (random packed bytes, constant scales and zeros: no quantizer run), scored for 64 seeded bit vectors
+        averaging about 3.5 bits on 4 calibration sequences of 2048 tokens each (one forward of 8192 rows per
+        vector through the stack, the head and the loss)."""
+        L_FULL, CANDS, SEQS = 32, SWEEP_VECTORS, SWEEP_SEQUENCES
         layers = []
         resident = 0
         for _ in range(L_FULL):
@@ -382,12 +408,17 @@ def main():
             layers.append(mats)
         full = fq.Stack(layers)
         vecs = [fq_synth.bit_vector(SEED + 10 + c, 7 * L_FULL, probs=(0.3, 0.3, 0.3, 0.1)) for c in range(CANDS)]
-        hid = torch.empty_like(x_fwd)
-        losses = torch.empty(M_FWD, dtype=torch.float32, device=dev)
+        rows = SEQS * M_FWD
+        x_seq = x_fwd.repeat(SEQS, 1) * torch.linspace(0.9, 1.1, SEQS, device=dev, dtype=torch.float16).repeat_interleave(M_FWD)[:, None]
+        lab_seq = labels.repeat(SEQS)
+        hid = torch.empty_like(x_seq)
+        losses = torch.empty(rows, dtype=torch.float32, device=dev)
+        ws_seq = torch.empty(fq.fq_stack_workspace_bytes(rows, HIDDEN, FFN), dtype=torch.uint8, device=dev)
+        ws_head_seq = torch.empty(fq.fq_head_nll_workspace_bytes(rows, VOCAB), dtype=torch.uint8, device=dev)
 
         def score(c):
-            fq.fq_stack_forward(full, vecs[c], x_fwd, out=hid, workspace=ws_fwd)
-            fq.fq_head_nll(hid, head, labels, out=losses, workspace=ws_head)
+            fq.fq_stack_forward(full, vecs[c], x_seq, out=hid, workspace=ws_seq)
+            fq.fq_head_nll(hid, head, lab_seq, out=losses, workspace=ws_head_seq)
 
         score(0)
         torch.cuda.synchronize()
@@ -396,10 +427,75 @@ def main():
             score(c)
         torch.cuda.synchronize()
         per = (time.perf_counter() - t0) / CANDS
-        flops = L_FULL * gemm_flops + head_flops
-        return {"blocks": L_FULL, "resident_GB": round(resident / 1e9, 2), "candidates": CANDS, "tokens": M_FWD,
-                "mean_bits": round(float(np.mean(np.concatenate(vecs))), 2), "ms_per_candidate_sequence": round(per * 1e3, 3),
-                "tflops": round(flops / per / 1e12, 1), "finite": bool(torch.isfinite(losses).all().item())}
+        flops = SEQS * (L_FULL * gemm_flops + head_flops)
+        return {"blocks": L_FULL, "resident_GB": round(resident / 1e9, 2), "bit_vectors": CANDS, "sequences": SEQS,
+                "tokens_per_sequence": M_FWD, "mean_bits": round(float(np.mean(np.concatenate(vecs))), 2),
+                "s_whole_sweep": round(per * CANDS, 3), "ms_per_bit_vector": round(per * 1e3, 3),
+                "tokens_per_s": round(rows / per, 1), "tflops": round(flops / per / 1e12, 1),
+                "finite": bool(torch.isfinite(losses).all().item())}
+
+    def random_matrix(N, K, bb):
+        """A packed matrix of random bytes with constant scales and zeros (no quantizer run)."""
+        nb, nm = fq.fq_packed_bytes(N, K, bb), fq.fq_meta_count(N, K)
+        return fq.PackedMatrix(torch.randint(0, 255, (nb,), dtype=torch.uint8, device=dev),
+                               torch.full((nm,), 0.01, dtype=torch.float16, device=dev),
+                               torch.full((nm,), float((1 << bb) // 2), dtype=torch.float16, device=dev), N, K, bb)
+
+    def leg_13b():
+        """A Llama-2-13B-shaped block (hidden 5120, FFN 13824) with bit-widths drawn 60/30/10 % from 2/3/4:
+        the seven dequant-GEMM launches and the block forward at M=4096, and decode at M=1 over 8 distinct
+        copies of the block (cold weights, more than the 256 MB last-level cache)."""
+        shapes13 = fq_synth.block_matrix_shapes(HIDDEN_13B, FFN_13B)
+        bv = fq_synth.bit_vector(SEED + 4, 7, probs=(0.6, 0.3, 0.1, 0.0))
+        copies = [[{int(bv[j]): random_matrix(N, K, int(bv[j]))} for j, (N, K) in enumerate(shapes13)]
+                  for _ in range(DECODE_LAYERS)]
+        flops13 = sum(2.0 * M_13B * N * K for N, K in shapes13)
+        bytes13 = sum(copies[0][j][int(bv[j])].nbytes + 2 * K + 2 * N for j, (N, K) in enumerate(shapes13))
+        xm = torch.empty((M_13B, HIDDEN_13B), dtype=torch.float16, device=dev).normal_()
+        xf = torch.empty((M_13B, FFN_13B), dtype=torch.float16, device=dev).normal_()
+        per_kernel, total = [], 0.0
+        for j, (N, K) in enumerate(shapes13):
+            w = copies[0][j][int(bv[j])]
+            o = torch.empty((M_13B, N), dtype=torch.float16, device=dev)
+            ms, ms_min = med_min(lambda: fq.fq_qlinear(xf if K == FFN_13B else xm, w, out=o))
+            total += ms
+            per_kernel.append({"matrix": fq_synth.MATRIX_NAMES[j], "N": N, "K": K, "bits": int(bv[j]), "ms": round(ms, 4),
+                               "ms_min": round(ms_min, 4), "tflops": round(2.0 * M_13B * N * K / ms / 1e9, 1)})
+        one = fq.Stack([copies[0]])
+        ws13 = torch.empty(fq.fq_stack_workspace_bytes(M_13B, HIDDEN_13B, FFN_13B), dtype=torch.uint8, device=dev)
+        ho = torch.empty_like(xm)
+        ms_blk, ms_blk_min = med_min(lambda: fq.fq_stack_forward(one, bv, xm, out=ho, workspace=ws13))
+        dec = fq.Stack(copies)
+        bv_dec = np.tile(bv, DECODE_LAYERS)
+        x1 = torch.empty((1, HIDDEN_13B), dtype=torch.float16, device=dev).normal_()
+        o1 = torch.empty_like(x1)
+        ws1 = torch.empty(fq.fq_stack_workspace_bytes(1, HIDDEN_13B, FFN_13B), dtype=torch.uint8, device=dev)
+        ms_d, ms_d_min = med_min(lambda: fq.fq_stack_forward(dec, bv_dec, x1, out=o1, workspace=ws1))
+        gbps = DECODE_LAYERS * bytes13 / ms_d / 1e6
+        return {"workload": "llama2-13b-block: bits %s (60/30/10 %% of 2/3/4), random packed bytes" % "/".join(map(str, bv)),
+                "gemm_m4096": {"tflops_kernels": round(flops13 / total / 1e9, 1),
+                               "frac_mfma_peak": round(flops13 / total / 1e9 / PEAK_MFMA_F16_TFLOPS, 4),
+                               "ms_block_forward": round(ms_blk, 4), "ms_block_forward_min": round(ms_blk_min, 4),
+                               "tflops_block_forward": round(flops13 / ms_blk / 1e9, 1), "kernels": per_kernel},
+                "gemv_m1": {"layers": DECODE_LAYERS, "MB_streamed": round(DECODE_LAYERS * bytes13 / 1e6, 1),
+                            "ms_stack_decode": round(ms_d, 4), "ms_stack_decode_min": round(ms_d_min, 4),
+                            "GBps_stack_decode": round(gbps, 1), "frac_hbm_peak": round(gbps / PEAK_HBM_GBPS, 4)}}
+
+    def leg_stream_read():
+        """The practical ceiling of the decode leg: the library's read-only kernel over a buffer as large as the
+        packed bytes one decode pass streams (cold: two such buffers alternate)."""
+        n = int(gemv_bytes) // 16 * 16
+        bufs = [torch.empty(n, dtype=torch.uint8, device=dev).random_(0, 255) for _ in range(2)]
+        sink = torch.empty(fq.STREAM_READ_WORDS, dtype=torch.int32, device=dev)
+        turn = [0]
+
+        def read():
+            fq.fq_stream_read(bufs[turn[0] & 1], sink)
+            turn[0] += 1
+
+        ms, ms_min = med_min(read)
+        return {"MB": round(n / 1e6, 1), "us": round(ms * 1e3, 2), "us_min": round(ms_min * 1e3, 2),
+                "GBps": round(n / ms / 1e6, 1), "frac_hbm_peak": round(n / ms / 1e6 / PEAK_HBM_GBPS, 4)}
 
     def leg_hbm_reference():
         """What plain device copies reach on this machine, as context for the HBM-bound figures: bytes read plus bytes
@@ -447,6 +543,8 @@ def main():
                 del cps, g1
         return table
 
+    block_13b = optional(leg_13b)
+    stream_read = optional(leg_stream_read)
     real_blocks = optional(leg_real_blocks)
     by_width = optional(leg_by_width)
     hbm_reference = optional(leg_hbm_reference)
@@ -461,8 +559,8 @@ def main():
     gemm_alg_bytes = sum(block[j][int(bitvec[j])].nbytes + 2.0 * M_FWD * (N + K) for j, (N, K) in enumerate(shapes))
 
     result = {
-        "metric": "dequant-GEMM TFLOP/s (M=2048) with dequant-GEMV GB/s (M=1) in legs, one Llama-2-7B block",
-        "value": round(step_flops / ms_per_step / 1e9, 2),
+        "metric": "dequant-GEMM TFLOP/s (M=2048) with dequant-GEMV GB/s (M=1) in roofline_gemv, one Llama-2-7B block",
+        "value": round(gemm_tflops, 2),
         "unit": "TFLOP/s",
         "n_gpus": 1,
         "steps": args.steps,
@@ -473,10 +571,14 @@ def main():
         "vs_baseline": None,
         "dtype": "f16",
         "data": "synthetic",
-        "config": {"workload": "llama2-7b-block: 7 linears, bits %s, group 128, M=2048 forward + fp16 head with fused NLL,"
-                               " M=1 decode over %d block copies" % ("/".join(map(str, bitvec)), DECODE_LAYERS),
+        "config": {"workload": "llama2-7b-block: 7 linears, bits %s, group 128; value = the seven dequant-GEMM launches at"
+                               " M=2048; a step = block forward M=2048 + fp16 head with fused NLL + M=1 decode over %d"
+                               " block copies" % ("/".join(map(str, bitvec)), DECODE_LAYERS),
                    "hidden": HIDDEN, "ffn": FFN, "vocab": VOCAB, "seed": SEED},
         "legs": {
+            "whole_step": {"tflops": round(step_flops / ms_per_step / 1e9, 2), "ms": round(ms_per_step, 4),
+                           "parts": "block forward M=2048 + head with fused NLL + decode M=1 over %d block copies" % DECODE_LAYERS},
+            "llama2_13b_block_outside_the_step": block_13b,
             "gemm_m2048": {"tflops_kernels": round(gemm_tflops, 1),
                            "tflops_block_forward": round(gemm_flops / ms_fwd_block / 1e9, 1),
                            "ms_block_forward": round(ms_fwd_block, 4), "frac_mfma_peak": round(gemm_tflops / PEAK_MFMA_F16_TFLOPS, 4)},
@@ -490,13 +592,15 @@ def main():
             "real_prefill_outside_the_step": real_blocks.get("prefill", real_blocks),
             "device_copy_reference_outside_the_step": hbm_reference,
             "every_shape_at_every_width_outside_the_step": by_width,
-            "full_stack_sweep_outside_the_step": full_stack,
+            "ensemble_sweep_outside_the_step": full_stack,
             "transition_outside_the_step": transition,
             "gemv_large_outside_the_step": gemv_large,
             "gemv_m1": {"GBps_single_launches": round(block_bytes / gemv_ms_total / 1e6, 1),
                         "GBps_stack_decode": round(gemv_bytes / ms_dec / 1e6, 1),
-                        "ms_stack_decode": round(ms_dec, 4), "layers": DECODE_LAYERS,
+                        "ms_stack_decode": round(ms_dec, 4), "ms_stack_decode_min": round(ms_dec_min, 4),
+                        "layers": DECODE_LAYERS, "MB_streamed": round(gemv_bytes / 1e6, 1),
                         "frac_hbm_peak": round(gemv_bytes / ms_dec / 1e6 / PEAK_HBM_GBPS, 4)},
+            "stream_read_of_the_decode_footprint": stream_read,
         },
         "kernels": {"gemm": kernels, "gemv": gemv_kernels},
         "roofline": {"bound": "mfma", "achieved": round(gemm_tflops, 1), "peak": PEAK_MFMA_F16_TFLOPS,
@@ -505,6 +609,8 @@ def main():
                      "algorithmic_flops": gemm_flops, "algorithmic_bytes": gemm_alg_bytes},
         "roofline_gemv": {"bound": "hbm", "achieved": round(gemv_bytes / ms_dec / 1e6, 1), "peak": PEAK_HBM_GBPS,
                           "unit": "GB/s", "frac": round(gemv_bytes / ms_dec / 1e6 / PEAK_HBM_GBPS, 4),
+                          "frac_of_stream_read": (round(gemv_bytes / ms_dec / 1e6 / stream_read["GBps"], 4)
+                                                  if "GBps" in stream_read else None),
                           "kernel": "gemv_stream_kernel (decode, M=1, 4 launches per block, launch gaps included)"},
     }
 

@@ -311,6 +311,17 @@ int fq_head_nll(const void *x, int M, const void *W, int V, int K, const int32_t
 int fq_logit_l2(const void *a, const void *b, int M, int V, float *dist_out, void *stream);
 
 /*
+ * Measurement aid, not a step of the method: reads `bytes` of device memory once
+ * (128-bit loads, nothing else) and leaves FQ_STREAM_READ_WORDS checksum words in
+ * sink.  Timing it gives the rate a pure read reaches on the device, the
+ * practical ceiling for the decode path, which streams every packed weight once
+ * per token (Section "Introduction").  src: device, 16-byte aligned, bytes a
+ * positive multiple of 16.  sink: device, FQ_STREAM_READ_WORDS uint32, written.
+ */
+#define FQ_STREAM_READ_WORDS 2048
+int fq_stream_read(const void *src, size_t bytes, uint32_t *sink, void *stream);
+
+/*
  * Real decoder blocks around the quantized linears, one decode step (the hosted
  * models of Section "Experiment" are Llama decoders; Section "Introduction":
  * served one token at a time).  Per block, for the token at position pos:

@@ -59,6 +59,7 @@ def _load() -> ctypes.CDLL:
         "fq_dequant": (ci, [vp, vp, vp, ci, ci, ci, ci, vp, ci, vp]),
         "fq_qlinear": (ci, [vp, ci, vp, vp, vp, ci, ci, ci, ci, vp, vp]),
         "fq_qlinear_tile": (ci, [vp, ci, vp, vp, vp, ci, ci, ci, ci, vp, ci, vp]),
+        "fq_stream_read": (ci, [vp, ctypes.c_size_t, vp, vp]),
         "fq_stack_workspace_bytes": (sz, [ci, ci, ci]),
         "fq_stack_forward": (ci, [ctypes.POINTER(fq_layer), ci, vp, vp, ci, vp, vp, sz, vp]),
         "fq_stack_forward_noalloc": (ci, [ctypes.POINTER(fq_layer), ci, vp, vp, ci, vp, vp]),
@@ -96,7 +97,7 @@ def _load() -> ctypes.CDLL:
 
 _lib = _load()
 EXPORTS = ("fq_last_error", "fq_version", "fq_quantize_rtn", "fq_packed_bytes", "fq_meta_count", "fq_pack_groups",
-           "fq_dequant", "fq_qlinear", "fq_qlinear_tile", "fq_stack_workspace_bytes", "fq_stack_forward", "fq_glue", "fq_dense_f16",
+           "fq_dequant", "fq_qlinear", "fq_qlinear_tile", "fq_stream_read", "fq_stack_workspace_bytes", "fq_stack_forward", "fq_glue", "fq_dense_f16",
            "fq_token_nll", "fq_logit_l2", "fq_head_nll_workspace_bytes", "fq_head_nll",
            "fq_attn_workspace_bytes", "fq_decode_workspace_bytes", "fq_attn_decode", "fq_decode_step",
            "fq_attn_prefill_workspace_bytes", "fq_prefill_workspace_bytes", "fq_attn_prefill", "fq_prefill_forward",
@@ -238,6 +239,18 @@ def fq_qlinear(x, w: PackedMatrix, out=None, stream=None, group: int = GROUP, ti
     _check(_lib.fq_qlinear_tile(_dp(x), M, _dp(w.packed), _dp(w.scales), _dp(w.zeros), w.N, w.K, w.bits, group,
                                 _dp(out), tile_rows, _stream(stream)))
     return out
+
+
+STREAM_READ_WORDS = 2048
+
+
+def fq_stream_read(src, sink=None, stream=None):
+    """Plain read of a device buffer (a measurement aid); returns the checksum words."""
+    torch = _torch()
+    if sink is None:
+        sink = torch.empty(STREAM_READ_WORDS, dtype=torch.int32, device=src.device)
+    _check(_lib.fq_stream_read(_dp(src), src.numel() * src.element_size(), _dp(sink), _stream(stream)))
+    return sink
 
 
 class Stack:

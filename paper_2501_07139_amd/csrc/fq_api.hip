@@ -226,6 +226,18 @@ extern "C" int fq_logit_l2(const void *a, const void *b, int M, int V, float *di
     return check_hip(fq_launch_logit_l2(a, b, M, V, dist_out, static_cast<fq_stream>(stream)), "fq_logit_l2 launch");
 }
 
+extern "C" int fq_stream_read(const void *src, size_t bytes, uint32_t *sink, void *stream)
+{
+    if (!src || !sink)
+        return fq_fail(FQ_ERR_NULL, "fq_stream_read: NULL argument");
+    if (bytes == 0 || bytes % 16 != 0)
+        return fq_fail(FQ_ERR_SHAPE, "fq_stream_read: %zu bytes (a positive multiple of 16)", bytes);
+    if (!aligned16(src))
+        return fq_fail(FQ_ERR_ALIGN, "fq_stream_read: src must be 16-byte aligned");
+    return check_hip(fq_launch_stream_read(src, bytes, sink, FQ_STREAM_READ_WORDS, static_cast<fq_stream>(stream)),
+                     "fq_stream_read launch");
+}
+
 // Shapes of the block's seven matrices and the selected packing of each, checked before anything is launched.
 static int validate_layers(const char *fn, const fq_layer *layers, int L, const uint8_t *bitvec, int *H_out, int *F_out)
 {

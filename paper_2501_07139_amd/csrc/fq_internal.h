@@ -86,5 +86,7 @@ int fq_launch_attn_prefill(const void *q, const void *k, const void *v, int T, v
 int fq_launch_glue(int op, const void *a, const void *b, const void *c, int M, int H, void *out, fq_stream st);
 int fq_launch_nll(const void *logits, const int32_t *labels, int M, int V, float *nll, fq_stream st);
 int fq_launch_logit_l2(const void *a, const void *b, int M, int V, float *dist, fq_stream st);
+// Plain read of a buffer; one word per workgroup lands in sink[blocks].
+int fq_launch_stream_read(const void *src, size_t bytes, uint32_t *sink, int blocks, fq_stream st);
 
 #endif

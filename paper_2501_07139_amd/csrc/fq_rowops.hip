@@ -265,3 +265,45 @@ int fq_launch_dequant(const fq_packed_ref &w, void *out, int out_is_fp16, fq_str
     }
     return (int)hipGetLastError();
 }
+
+// ------------------------------------------------------------ streaming read
+// Reads `bytes` once with 128-bit loads, eight independent loads per lane and round, and keeps one word
+// per workgroup: what a kernel that does nothing but read reaches on this device, the practical ceiling
+// beside which the decode path's bytes per second are reported (Section "Introduction": single-batch
+// decoding streams every weight once per token and is bound by that).
+namespace {
+__global__ __launch_bounds__(256) void stream_read_kernel(const u4v *__restrict__ src, size_t n16, uint32_t *sink)
+{
+    const size_t stride = (size_t)gridDim.x * 256;
+    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    u4v acc = {0u, 0u, 0u, 0u};
+    for (; i + 7 * stride < n16; i += 8 * stride) {
+        u4v v[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k)
+            v[k] = __builtin_nontemporal_load(src + i + k * stride);
+#pragma unroll
+        for (int k = 0; k < 8; ++k)
+            acc ^= v[k];
+    }
+    for (; i < n16; i += stride)
+        acc ^= __builtin_nontemporal_load(src + i);
+    uint32_t w = acc.x ^ acc.y ^ acc.z ^ acc.w;
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1)
+        w ^= __shfl_xor(w, o, 64);
+    __shared__ uint32_t part[4];
+    if ((threadIdx.x & 63) == 0)
+        part[threadIdx.x >> 6] = w;
+    __syncthreads();
+    if (threadIdx.x == 0)
+        sink[blockIdx.x] = part[0] ^ part[1] ^ part[2] ^ part[3];
+}
+} // namespace
+
+int fq_launch_stream_read(const void *src, size_t bytes, uint32_t *sink, int blocks, fq_stream st)
+{
+    hipLaunchKernelGGL(stream_read_kernel, dim3(blocks), dim3(256), 0, st, static_cast<const u4v *>(src), bytes / 16, sink);
+    return (int)hipGetLastError();
+}
+

@@ -742,3 +742,18 @@ def test_head_nll_stays_inside_output_and_workspace(fq, torch, case):
     with pytest.raises(fq.FqError) as e:
         fq.fq_head_nll(X, W, lab, workspace=ws.bytes()[:need - 16])
     assert e.value.code == -6
+
+
+def test_stream_read_reads_every_word_once(fq, torch):
+    """The read-only measurement kernel: the XOR of its checksum words is the XOR of all 32-bit words of the
+    buffer, whatever the split over workgroups (a size with a ragged tail of 16-byte units)."""
+    n = (3 << 20) + 16 * 37
+    rng = np.random.default_rng(5)
+    host = rng.integers(0, 2 ** 32, size=n // 4, dtype=np.uint32)
+    buf = torch.from_numpy(host.view(np.int32)).cuda()
+    sink = fq.fq_stream_read(buf)
+    torch.cuda.synchronize()
+    got = np.bitwise_xor.reduce(sink.cpu().numpy().view(np.uint32))
+    assert got == np.bitwise_xor.reduce(host)
+    with pytest.raises(fq.FqError):
+        fq.fq_stream_read(buf[:3])
