@@ -128,8 +128,9 @@ extern "C" int fq_quantize_rtn(const float *W, int N, int K, int bits, int group
                 float zr = std::nearbyintf((0.0f - mn) / s); // 0 - 0 is +0: the stored zero is never -0
                 zr = std::min(std::max(zr, 0.0f), qmax);
                 for (int i = 0; i < 128; ++i) {
-                    float c = std::nearbyintf(w[i] / s);
-                    c = std::min(std::max(c, -1.0e6f), 1.0e6f) + zr; // integers: exact
+                    // stays in floating point until it is inside [0, qmax]: the sum of two integers is exact
+                    // wherever it can land in that range, and no out-of-range value is converted
+                    const float c = std::nearbyintf(w[i] / s) + zr;
                     q[i] = (uint8_t)std::min(std::max(c, 0.0f), qmax);
                 }
                 scales[mi] = sh;
