@@ -391,8 +391,10 @@ static int stack_forward_checked(const fq_layer *layers, int L, const uint8_t *b
         void *const gp[2] = {g, p};
         int rc;
 #define FQ_STEP(call) \
-    if ((rc = (call)) != FQ_OK) \
-        return rc
+    do { \
+        if ((rc = (call)) != FQ_OK) \
+            return rc; \
+    } while (0)
         if (decode) {
             // the previous block's x_next = rms(x1 + d) is produced (into xc) by this block's first launch
             const fq_gemv_input in_qkv = (l == 0) ? fq_gemv_input{x_in, nullptr, nullptr, nullptr, 1}
@@ -410,16 +412,23 @@ static int stack_forward_checked(const fq_layer *layers, int L, const uint8_t *b
                 FQ_STEP(check_hip(fq_launch_glue(4, x1, d, nullptr, M, H, x_out, st), "glue rms(add)"));
             continue;
         }
-        FQ_STEP(check_hip(fq_launch_glue(0, xcur, nullptr, nullptr, M, H, u, st), "glue rms"));
+        // M > 16: the row-wise steps are kernels of their own, two of them per pass where one feeds the other
+        // (the residual sum with the norm that reads it; a block's output with the next block's first norm)
+        if (l == 0) {
+            FQ_STEP(check_hip(fq_launch_glue(0, xcur, nullptr, nullptr, M, H, u, st), "glue rms"));
+        }
         FQ_STEP(qlinear_multi_checked(u, M, &sel[0], qkv, 3, st));
         FQ_STEP(check_hip(fq_launch_glue(1, q, k, v, M, H, a, st), "glue rms(q+k+v)"));
         FQ_STEP(qlinear_checked(a, M, sel[3], o, st));
-        FQ_STEP(check_hip(fq_launch_glue(2, xcur, o, nullptr, M, H, x1, st), "glue add"));
-        FQ_STEP(check_hip(fq_launch_glue(0, x1, nullptr, nullptr, M, H, u2, st), "glue rms"));
+        FQ_STEP(check_hip(fq_launch_glue2(6, xcur, o, M, H, x1, u2, st), "glue add, rms"));
         FQ_STEP(qlinear_multi_checked(u2, M, &sel[4], gp, 2, st));
         FQ_STEP(check_hip(fq_launch_glue(3, g, p, nullptr, M, F, mm, st), "glue rms(silu*mul)"));
         FQ_STEP(qlinear_checked(mm, M, sel[6], d, st));
-        FQ_STEP(check_hip(fq_launch_glue(4, x1, d, nullptr, M, H, xnext, st), "glue rms(add)"));
+        if (l == L - 1) {
+            FQ_STEP(check_hip(fq_launch_glue(4, x1, d, nullptr, M, H, xnext, st), "glue rms(add)"));
+        } else {
+            FQ_STEP(check_hip(fq_launch_glue2(7, x1, d, M, H, xnext, u, st), "glue rms(add), rms"));
+        }
 #undef FQ_STEP
         xcur = xnext;
     }
@@ -502,8 +511,10 @@ extern "C" int fq_decode_step(const fq_layer *layers, int L, const uint8_t *bitv
         void *const gp[2] = {g, p};
         int rc;
 #define FQ_STEP(call) \
-    if ((rc = (call)) != FQ_OK) \
-        return rc
+    do { \
+        if ((rc = (call)) != FQ_OK) \
+            return rc; \
+    } while (0)
         // the previous block's output x1 + d is formed (into xc) by this block's first launch
         const fq_gemv_input in_qkv = (l == 0) ? fq_gemv_input{x_in, nullptr, nullptr, nullptr, 1}
                                               : fq_gemv_input{x1, d, nullptr, xc, 3};
@@ -598,8 +609,10 @@ extern "C" int fq_prefill_forward(const fq_layer *layers, int L, const uint8_t *
         void *const gp[2] = {g, p};
         int rc;
 #define FQ_STEP(call) \
-    if ((rc = (call)) != FQ_OK) \
-        return rc
+    do { \
+        if ((rc = (call)) != FQ_OK) \
+            return rc; \
+    } while (0)
         FQ_STEP(check_hip(fq_launch_glue(0, xcur, nullptr, nullptr, M, H, u, st), "glue rms"));
         if (M > 16) {
             FQ_STEP(qlinear_multi_checked(u, M, &sel[0], qkv, 3, st));
@@ -611,8 +624,7 @@ extern "C" int fq_prefill_forward(const fq_layer *layers, int L, const uint8_t *
                                                  static_cast<char *>(v_cache) + l * layer_cache, Tmax, n_heads, rope, a,
                                                  attn, st), "prefill attention"));
         FQ_STEP(qlinear_checked(a, M, sel[3], o, st));
-        FQ_STEP(check_hip(fq_launch_glue(2, xcur, o, nullptr, M, H, x1, st), "glue add"));
-        FQ_STEP(check_hip(fq_launch_glue(0, x1, nullptr, nullptr, M, H, u, st), "glue rms"));
+        FQ_STEP(check_hip(fq_launch_glue2(6, xcur, o, M, H, x1, u, st), "glue add, rms"));
         if (M > 16) {
             FQ_STEP(qlinear_multi_checked(u, M, &sel[4], gp, 2, st));
         } else {

@@ -84,6 +84,8 @@ size_t fq_attn_prefill_scratch_bytes(int T, int n_heads);
 int fq_launch_attn_prefill(const void *q, const void *k, const void *v, int T, void *k_cache, void *v_cache,
                            int Tmax, int n_heads, const float *rope, void *out, void *workspace, fq_stream st);
 int fq_launch_glue(int op, const void *a, const void *b, const void *c, int M, int H, void *out, fq_stream st);
+// Two steps in one pass: op 6: aux = a + b, out = rms(aux); op 7: aux = rms(a + b), out = rms(aux).
+int fq_launch_glue2(int op, const void *a, const void *b, int M, int H, void *aux, void *out, fq_stream st);
 int fq_launch_nll(const void *logits, const int32_t *labels, int M, int V, float *nll, fq_stream st);
 int fq_launch_logit_l2(const void *a, const void *b, int M, int V, float *dist, fq_stream st);
 // Plain read of a buffer; one word per workgroup lands in sink[blocks].

@@ -90,6 +90,72 @@ __global__ __launch_bounds__(256) void glue_kernel(const _Float16 *__restrict__ 
     }
 }
 
+// Two consecutive row-wise steps of the block in one pass (M > 16), each rounded to fp16 where the separate
+// kernels would store it, so the values are those of the two calls:
+//   OP 6: aux = a + b,       out = rms(aux)     the residual after the output projection and the FFN's input
+//   OP 7: aux = rms(a + b),  out = rms(aux)     a block's output and the next block's first normalisation
+template <int OP>
+__global__ __launch_bounds__(256) void glue2_kernel(const _Float16 *__restrict__ a, const _Float16 *__restrict__ b, int H,
+                                                    _Float16 *__restrict__ aux, _Float16 *__restrict__ out)
+{
+    const size_t row = (size_t)blockIdx.x * H;
+    const int chunks = H >> 3;
+    __shared__ float part[2][4];
+    auto row_sum = [&](float ss, int which) {
+        ss = wave_sum(ss);
+        if ((threadIdx.x & 63) == 0)
+            part[which][threadIdx.x >> 6] = ss;
+        __syncthreads();
+        return part[which][0] + part[which][1] + part[which][2] + part[which][3];
+    };
+    float t[GLUE_MAXC][8];
+    float ss = 0.f;
+#pragma unroll
+    for (int i = 0; i < GLUE_MAXC; ++i) {
+        const int ch = threadIdx.x + 256 * i;
+        if (ch < chunks) {
+            const h8 va = *reinterpret_cast<const h8 *>(a + row + ch * 8), vb = *reinterpret_cast<const h8 *>(b + row + ch * 8);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                float v = (float)va[e] + (float)vb[e];
+                if constexpr (OP == 6)
+                    v = (float)(_Float16)v; // the stored sum is what the norm reads
+                t[i][e] = v;
+                ss += v * v;
+            }
+        }
+    }
+    if constexpr (OP == 7) { // first norm; its rounded result is the second one's input
+        const float inv = 1.0f / sqrtf(row_sum(ss, 0) / (float)H + 1e-5f);
+        ss = 0.f;
+#pragma unroll
+        for (int i = 0; i < GLUE_MAXC; ++i)
+            if (threadIdx.x + 256 * i < chunks) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const float v = (float)(_Float16)(t[i][e] * inv);
+                    t[i][e] = v;
+                    ss += v * v;
+                }
+            }
+    }
+    const float inv = 1.0f / sqrtf(row_sum(ss, 1) / (float)H + 1e-5f);
+#pragma unroll
+    for (int i = 0; i < GLUE_MAXC; ++i) {
+        const int ch = threadIdx.x + 256 * i;
+        if (ch < chunks) {
+            h8 x, o;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                x[e] = (_Float16)t[i][e]; // exact: already an fp16 value
+                o[e] = (_Float16)(t[i][e] * inv);
+            }
+            *reinterpret_cast<h8 *>(aux + row + ch * 8) = x;
+            *reinterpret_cast<h8 *>(out + row + ch * 8) = o;
+        }
+    }
+}
+
 // ------------------------------------------------------------------- NLL
 // One workgroup per token row; each thread keeps a running (max, sum of
 // exp(l - max)) over its 16-byte chunks, then the pairs are merged across the
@@ -196,6 +262,17 @@ int fq_launch_glue(int op, const void *a, const void *b, const void *c, int M, i
     case 4: hipLaunchKernelGGL(glue_kernel<4>, grid, block, 0, st, pa, pb, pc, H, po); break;
     default: hipLaunchKernelGGL(glue_kernel<5>, grid, block, 0, st, pa, pb, pc, H, po); break;
     }
+    return (int)hipGetLastError();
+}
+
+int fq_launch_glue2(int op, const void *a, const void *b, int M, int H, void *aux, void *out, fq_stream st)
+{
+    dim3 grid(M), block(256);
+    const _Float16 *pa = static_cast<const _Float16 *>(a), *pb = static_cast<const _Float16 *>(b);
+    if (op == 6)
+        hipLaunchKernelGGL(glue2_kernel<6>, grid, block, 0, st, pa, pb, H, static_cast<_Float16 *>(aux), static_cast<_Float16 *>(out));
+    else
+        hipLaunchKernelGGL(glue2_kernel<7>, grid, block, 0, st, pa, pb, H, static_cast<_Float16 *>(aux), static_cast<_Float16 *>(out));
     return (int)hipGetLastError();
 }
 
