@@ -481,6 +481,35 @@ def main():
                             "ms_stack_decode": round(ms_d, 4), "ms_stack_decode_min": round(ms_d_min, 4),
                             "GBps_stack_decode": round(gbps, 1), "frac_hbm_peak": round(gbps / PEAK_HBM_GBPS, 4)}}
 
+    def leg_mixed_matrix():
+        """Widths mixed within one matrix: a 4096 x 4096 matrix stored as three runs of output rows (60 % at
+        2 bits, 30 % at 3, 10 % at 4: 2.5 bits on average), decode (M=1, rotating over cold copies) and M=2048."""
+        runs = [(2432, 2), (1232, 3), (432, 4)]
+        one_bytes = sum(fq.fq_packed_bytes(N, HIDDEN, bb) + 4 * fq.fq_meta_count(N, HIDDEN) for N, bb in runs)
+        copies = -(-ROTATE_BYTES // one_bytes)
+        mats = [[random_matrix(N, HIDDEN, bb) for N, bb in runs] for _ in range(copies)]
+        x1 = torch.empty((1, HIDDEN), dtype=torch.float16, device=dev).normal_()
+        o1 = torch.empty((1, HIDDEN), dtype=torch.float16, device=dev)
+
+        def rot():
+            for segs in mats:
+                fq.fq_qlinear_mixed(x1, segs, out=o1)
+
+        rot()
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            rot()
+        us, us_min = med_min(graph.replay, per=copies)
+        xm = torch.empty((M_FWD, HIDDEN), dtype=torch.float16, device=dev).normal_()
+        om = torch.empty((M_FWD, HIDDEN), dtype=torch.float16, device=dev)
+        ms, ms_min = med_min(lambda: fq.fq_qlinear_mixed(xm, mats[0], out=om))
+        return {"N": HIDDEN, "K": HIDDEN, "runs": [{"rows": N, "bits": bb} for N, bb in runs],
+                "mean_bits": round(sum(N * bb for N, bb in runs) / HIDDEN, 2), "copies": copies,
+                "gemv_us": round(us * 1e3, 2), "gemv_us_min": round(us_min * 1e3, 2),
+                "gemv_GBps": round(one_bytes / us / 1e6, 1), "gemm_ms": round(ms, 4), "gemm_ms_min": round(ms_min, 4),
+                "gemm_tflops": round(2.0 * M_FWD * HIDDEN * HIDDEN / ms / 1e9, 1)}
+
     def leg_stream_read():
         """The practical ceiling of the decode leg: the library's read-only kernel over a buffer as large as the
         packed bytes one decode pass streams (cold: two such buffers alternate)."""
@@ -544,6 +573,7 @@ def main():
         return table
 
     block_13b = optional(leg_13b)
+    mixed_matrix = optional(leg_mixed_matrix)
     stream_read = optional(leg_stream_read)
     real_blocks = optional(leg_real_blocks)
     by_width = optional(leg_by_width)
@@ -579,6 +609,7 @@ def main():
             "whole_step": {"tflops": round(step_flops / ms_per_step / 1e9, 2), "ms": round(ms_per_step, 4),
                            "parts": "block forward M=2048 + head with fused NLL + decode M=1 over %d block copies" % DECODE_LAYERS},
             "llama2_13b_block_outside_the_step": block_13b,
+            "mixed_widths_within_a_matrix_outside_the_step": mixed_matrix,
             "gemm_m2048": {"tflops_kernels": round(gemm_tflops, 1),
                            "tflops_block_forward": round(gemm_flops / ms_fwd_block / 1e9, 1),
                            "ms_block_forward": round(ms_fwd_block, 4), "frac_mfma_peak": round(gemm_tflops / PEAK_MFMA_F16_TFLOPS, 4)},

@@ -156,6 +156,29 @@ int fq_qlinear(const void *x, int M, const void *packed, const void *scales, con
 int fq_qlinear_tile(const void *x, int M, const void *packed, const void *scales, const void *zeros,
                     int N, int K, int bits, int group, void *out, int tile_rows, void *stream);
 
+/*
+ * Mixed precision WITHIN a matrix (Section "Large Language Model Quantization":
+ * the quantizers the paper builds on assign different bit-widths not only across
+ * modules but within individual modules).  Here a matrix [N,K] is stored as up to
+ * FQ_MAX_SEGMENTS runs of consecutive output rows, each run a packed triple of
+ * its own bit-width over the same K, and
+ *   out[m, n0_i + n] = fq_qlinear(x, segment i)[m, n],  n0_i = N_0 + ... + N_(i-1),
+ * the same arithmetic as fq_qlinear per run; out fp16 [M, sum of N_i] row-major.
+ * Runs that share a launch (three at a time) are dealt to the chip together, like
+ * q/k/v in the stack forward.  Any M >= 1; every N_i >= 1 (no alignment needed:
+ * each run is padded on its own); segments: host array, device pointers inside.
+ * (The cited quantizers vary the width along the input dimension; this format
+ * keeps a row's groups at one width, so the variation is along the output rows.)
+ */
+#define FQ_MAX_SEGMENTS 8
+typedef struct {
+    const void *packed, *scales, *zeros; /* device: the packed triple of this run of rows */
+    int N;                               /* rows (output features) of the run */
+    int bits;                            /* 2, 3, 4 or 8 */
+} fq_segment;
+int fq_qlinear_mixed(const void *x, int M, const fq_segment *segments, int count, int K, int group, void *out,
+                     void *stream);
+
 /* One matrix in all stored bit-widths; index 0..3 = bits 2, 3, 4, 8.  Unused widths may be NULL. */
 typedef struct {
     const void *packed[4];

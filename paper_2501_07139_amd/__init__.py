@@ -60,6 +60,7 @@ def _load() -> ctypes.CDLL:
         "fq_qlinear": (ci, [vp, ci, vp, vp, vp, ci, ci, ci, ci, vp, vp]),
         "fq_qlinear_tile": (ci, [vp, ci, vp, vp, vp, ci, ci, ci, ci, vp, ci, vp]),
         "fq_stream_read": (ci, [vp, ctypes.c_size_t, vp, vp]),
+        "fq_qlinear_mixed": (ci, [vp, ci, vp, ci, ci, ci, vp, vp]),
         "fq_stack_workspace_bytes": (sz, [ci, ci, ci]),
         "fq_stack_forward": (ci, [ctypes.POINTER(fq_layer), ci, vp, vp, ci, vp, vp, sz, vp]),
         "fq_stack_forward_noalloc": (ci, [ctypes.POINTER(fq_layer), ci, vp, vp, ci, vp, vp]),
@@ -97,7 +98,7 @@ def _load() -> ctypes.CDLL:
 
 _lib = _load()
 EXPORTS = ("fq_last_error", "fq_version", "fq_quantize_rtn", "fq_packed_bytes", "fq_meta_count", "fq_pack_groups",
-           "fq_dequant", "fq_qlinear", "fq_qlinear_tile", "fq_stream_read", "fq_stack_workspace_bytes", "fq_stack_forward", "fq_glue", "fq_dense_f16",
+           "fq_dequant", "fq_qlinear", "fq_qlinear_tile", "fq_qlinear_mixed", "fq_stream_read", "fq_stack_workspace_bytes", "fq_stack_forward", "fq_glue", "fq_dense_f16",
            "fq_token_nll", "fq_logit_l2", "fq_head_nll_workspace_bytes", "fq_head_nll",
            "fq_attn_workspace_bytes", "fq_decode_workspace_bytes", "fq_attn_decode", "fq_decode_step",
            "fq_attn_prefill_workspace_bytes", "fq_prefill_workspace_bytes", "fq_attn_prefill", "fq_prefill_forward",
@@ -238,6 +239,32 @@ def fq_qlinear(x, w: PackedMatrix, out=None, stream=None, group: int = GROUP, ti
     _dev(out, torch.float16, "out")
     _check(_lib.fq_qlinear_tile(_dp(x), M, _dp(w.packed), _dp(w.scales), _dp(w.zeros), w.N, w.K, w.bits, group,
                                 _dp(out), tile_rows, _stream(stream)))
+    return out
+
+
+MAX_SEGMENTS = 8
+
+
+class _Segment(ctypes.Structure):
+    _fields_ = [("packed", ctypes.c_void_p), ("scales", ctypes.c_void_p), ("zeros", ctypes.c_void_p),
+                ("N", ctypes.c_int), ("bits", ctypes.c_int)]
+
+
+def fq_qlinear_mixed(x, segments, out=None, stream=None, group: int = GROUP):
+    """One matrix stored as runs of output rows, each a PackedMatrix of its own bit-width over the same K."""
+    torch = _torch()
+    x = _dev(x, torch.float16, "x")
+    M, K = x.shape
+    if not 1 <= len(segments) <= MAX_SEGMENTS:
+        raise FqError(-2, f"{len(segments)} segments (1..{MAX_SEGMENTS})")
+    if any(w.K != K for w in segments):
+        raise FqError(-2, "every segment must have the K of x")
+    arr = (_Segment * len(segments))(*[_Segment(_dp(w.packed), _dp(w.scales), _dp(w.zeros), w.N, w.bits) for w in segments])
+    if out is None:
+        out = torch.empty((M, sum(w.N for w in segments)), dtype=torch.float16, device=x.device)
+    _dev(out, torch.float16, "out")
+    _check(_lib.fq_qlinear_mixed(_dp(x), M, ctypes.cast(arr, ctypes.c_void_p), len(segments), K, group, _dp(out),
+                                 _stream(stream)))
     return out
 
 

@@ -131,6 +131,58 @@ extern "C" int fq_qlinear_tile(const void *x, int M, const void *packed, const v
     return qlinear_checked(x, M, w, out, static_cast<fq_stream>(stream), tile_rows);
 }
 
+extern "C" int fq_qlinear_mixed(const void *x, int M, const fq_segment *segments, int count, int K, int group,
+                                void *out, void *stream)
+{
+    if (!segments || !x || !out)
+        return fq_fail(FQ_ERR_NULL, "fq_qlinear_mixed: NULL argument");
+    if (count < 1 || count > FQ_MAX_SEGMENTS)
+        return fq_fail(FQ_ERR_SHAPE, "fq_qlinear_mixed: %d segments (1..%d)", count, FQ_MAX_SEGMENTS);
+    if (M <= 0)
+        return fq_fail(FQ_ERR_SHAPE, "fq_qlinear_mixed: M=%d", M);
+    if (!aligned16(x) || !aligned16(out))
+        return fq_fail(FQ_ERR_ALIGN, "fq_qlinear_mixed: x and out must be 16-byte aligned");
+    long total = 0;
+    for (int i = 0; i < count; ++i) {
+        const fq_segment &sg = segments[i];
+        if (int rc = check_matrix("fq_qlinear_mixed", sg.packed, sg.scales, sg.zeros, sg.N, K, sg.bits, group))
+            return rc;
+        if (M > 16 && (!below_4gib(M, K, 2) || !below_4gib(((size_t)sg.N + 63) / 64 * 8, K, sg.bits)))
+            return fq_fail(FQ_ERR_SHAPE, "fq_qlinear_mixed: M=%d N=%d K=%d: activations and packed weights must each "
+                           "stay below 4 GiB", M, sg.N, K);
+        total += sg.N;
+    }
+    if (total > (1L << 30))
+        return fq_fail(FQ_ERR_SHAPE, "fq_qlinear_mixed: %ld output columns", total);
+    fq_stream st = static_cast<fq_stream>(stream);
+    fq_packed_ref w[FQ_MAX_SEGMENTS];
+    void *outs[FQ_MAX_SEGMENTS];
+    bool stream_all = M <= 16;
+    long col = 0;
+    for (int i = 0; i < count; ++i) {
+        w[i] = fq_packed_ref{segments[i].packed, segments[i].scales, segments[i].zeros, segments[i].N, K,
+                             segments[i].bits, (int)total};
+        outs[i] = static_cast<_Float16 *>(out) + col; // row 0 of the segment's column range; rows are `total` apart
+        col += segments[i].N;
+        stream_all = stream_all && fq_gemv_can_stream(M, K, segments[i].bits, 1);
+    }
+    // up to three segments share a launch (they share x): the same multi-matrix launches q/k/v and gate/up use
+    for (int i = 0; i < count; i += 3) {
+        const int n = count - i < 3 ? count - i : 3;
+        int e = 0;
+        if (M > 16)
+            e = fq_launch_gemm_multi(x, M, &w[i], &outs[i], n, st, 128);
+        else if (stream_all)
+            e = fq_launch_gemv_multi(fq_gemv_input{x, nullptr, nullptr, nullptr, 0}, M, &w[i], &outs[i], n, st);
+        else
+            for (int j = i; j < i + n && e == 0; ++j)
+                e = fq_launch_gemv(x, M, w[j], outs[j], st);
+        if (int rc = check_hip(e, "fq_qlinear_mixed launch"))
+            return rc;
+    }
+    return FQ_OK;
+}
+
 extern "C" int fq_init(void)
 {
     if (int rc = check_hip(fq_gemv_prepare(), "fq_init"))

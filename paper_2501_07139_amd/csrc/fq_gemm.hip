@@ -85,7 +85,7 @@ template <int BITS, int QNB>
 __device__ __forceinline__ void qgemm_tile(h8 (*Xs)[QBM * 16], const _Float16 *__restrict__ x, int M,
                                            const uint32_t *__restrict__ packed, const _Float16 *__restrict__ scales,
                                            const _Float16 *__restrict__ zeros, int N, int K,
-                                           _Float16 *__restrict__ out, int tile)
+                                           _Float16 *__restrict__ out, int ld, int tile)
 {
     constexpr int QBN = 64 * QNB;
     const int tid = threadIdx.x;
@@ -271,7 +271,9 @@ __device__ __forceinline__ void qgemm_tile(h8 (*Xs)[QBM * 16], const _Float16 *_
     else
         pipelined_loop(std::false_type{});
 
-    // store: lane holds m = lane%16 and n = 4*(lane/16) + v of each 16x16 block
+    // store: lane holds m = lane%16 and n = 4*(lane/16) + v of each 16x16 block; four values at once where
+    // every row of the output (a column range of a wider array when ld > N) starts 8-byte aligned
+    const bool vec_ok = (ld & 3) == 0 && (reinterpret_cast<uintptr_t>(out) & 7) == 0;
 #pragma unroll
     for (int j = 0; j < QMB; ++j) {
         const int m = m0 + j * 16 + (lane & 15);
@@ -280,8 +282,8 @@ __device__ __forceinline__ void qgemm_tile(h8 (*Xs)[QBM * 16], const _Float16 *_
 #pragma unroll
         for (int i = 0; i < QNB; ++i) {
             const int n = (rb0 + i) * 16 + 4 * (lane >> 4);
-            _Float16 *o = out + (size_t)m * N + n;
-            if (n + 3 < N && (N & 3) == 0) {
+            _Float16 *o = out + (size_t)m * ld + n;
+            if (n + 3 < N && vec_ok) {
                 h4 v = {(_Float16)acc[i][j][0], (_Float16)acc[i][j][1], (_Float16)acc[i][j][2], (_Float16)acc[i][j][3]};
                 *reinterpret_cast<h4 *>(o) = v;
             } else {
@@ -317,7 +319,7 @@ __global__ __launch_bounds__(256, 2) void qgemm_kernel(const _Float16 *__restric
     const int tile = xcd_tile(((N + QBN - 1) / QBN) * ((M + QBM - 1) / QBM));
     if (tile < 0)
         return; // before any barrier
-    qgemm_tile<BITS, QNB>(Xs, x, M, packed, scales, zeros, N, K, out, tile);
+    qgemm_tile<BITS, QNB>(Xs, x, M, packed, scales, zeros, N, K, out, N, tile);
 }
 
 // Up to three matrices with the same input in one launch (q/k/v, gate/up): their tiles form one list, so
@@ -329,6 +331,7 @@ struct GemmJob {
     const _Float16 *scales, *zeros;
     _Float16 *out;
     int N, bits, qnb, tile0; // tile0: index of the matrix's first tile in the launch's list
+    int ld;                  // elements between consecutive rows of out
 };
 struct GemmJobs {
     GemmJob j[3];
@@ -349,12 +352,12 @@ __global__ __launch_bounds__(256, 2) void qgemm_multi_kernel(const _Float16 *__r
     const GemmJob job = ji == 0 ? jobs.j[0] : (ji == 1 ? jobs.j[1] : jobs.j[2]); // selected by value
     tile -= job.tile0;
     switch (job.bits * 8 + job.qnb) {
-    case 2 * 8 + 4: qgemm_tile<2, 4>(Xs, x, M, job.packed, job.scales, job.zeros, job.N, K, job.out, tile); break;
-    case 4 * 8 + 4: qgemm_tile<4, 4>(Xs, x, M, job.packed, job.scales, job.zeros, job.N, K, job.out, tile); break;
-    case 2 * 8 + 2: qgemm_tile<2, 2>(Xs, x, M, job.packed, job.scales, job.zeros, job.N, K, job.out, tile); break;
-    case 3 * 8 + 2: qgemm_tile<3, 2>(Xs, x, M, job.packed, job.scales, job.zeros, job.N, K, job.out, tile); break;
-    case 4 * 8 + 2: qgemm_tile<4, 2>(Xs, x, M, job.packed, job.scales, job.zeros, job.N, K, job.out, tile); break;
-    default: qgemm_tile<8, 2>(Xs, x, M, job.packed, job.scales, job.zeros, job.N, K, job.out, tile); break;
+    case 2 * 8 + 4: qgemm_tile<2, 4>(Xs, x, M, job.packed, job.scales, job.zeros, job.N, K, job.out, job.ld, tile); break;
+    case 4 * 8 + 4: qgemm_tile<4, 4>(Xs, x, M, job.packed, job.scales, job.zeros, job.N, K, job.out, job.ld, tile); break;
+    case 2 * 8 + 2: qgemm_tile<2, 2>(Xs, x, M, job.packed, job.scales, job.zeros, job.N, K, job.out, job.ld, tile); break;
+    case 3 * 8 + 2: qgemm_tile<3, 2>(Xs, x, M, job.packed, job.scales, job.zeros, job.N, K, job.out, job.ld, tile); break;
+    case 4 * 8 + 2: qgemm_tile<4, 2>(Xs, x, M, job.packed, job.scales, job.zeros, job.N, K, job.out, job.ld, tile); break;
+    default: qgemm_tile<8, 2>(Xs, x, M, job.packed, job.scales, job.zeros, job.N, K, job.out, job.ld, tile); break;
     }
 }
 
@@ -761,6 +764,9 @@ static bool fits_32bit(size_t a, size_t b, size_t elem_bytes) { return a * b * e
 
 static int launch_tall(const void *x, int M, const fq_packed_ref *w, void *const *outs, int count, fq_stream st)
 {
+    for (int i = 0; i < count; ++i)
+        if (w[i].ld && w[i].ld != w[i].N)
+            return (int)hipErrorInvalidValue; // this kernel writes outputs of their own only
     TallJobs jobs;
     jobs.count = count;
     int total = 0;
@@ -783,6 +789,8 @@ int fq_launch_gemm(const void *x, int M, const fq_packed_ref &w, void *out, fq_s
         return (int)hipErrorInvalidValue;
     if (tile_rows == 256) // never the library's own choice: as measured the 128-row kernels are faster
         return launch_tall(x, M, &w, &out, 1, st);
+    if (w.ld && w.ld != w.N) // a column range of a wider output: the multi-matrix kernel carries the row pitch
+        return fq_launch_gemm_multi(x, M, &w, &out, 1, st, 128);
     switch (w.bits) {
     case 2: return launch_q<2>(x, M, w, out, st);
     case 3: return launch_q<3>(x, M, w, out, st);
@@ -811,7 +819,7 @@ int fq_launch_gemm_multi(const void *x, int M, const fq_packed_ref *w, void *con
         const int qnb = ((w[i].bits == 2 || w[i].bits == 4) && wide_tiles_pay(M, w[i].N)) ? 4 : 2;
         jobs.j[i] = GemmJob{static_cast<const uint32_t *>(w[i].packed), static_cast<const _Float16 *>(w[i].scales),
                             static_cast<const _Float16 *>(w[i].zeros), static_cast<_Float16 *>(outs[i]), w[i].N,
-                            w[i].bits, qnb, total};
+                            w[i].bits, qnb, total, w[i].ld ? w[i].ld : w[i].N};
         total += ((w[i].N + 64 * qnb - 1) / (64 * qnb)) * ((M + QBM - 1) / QBM);
     }
     jobs.total = total;

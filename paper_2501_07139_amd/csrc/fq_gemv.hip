@@ -46,7 +46,7 @@ __global__ __launch_bounds__(64 * NWAVES) void gemv_generic_kernel(const _Float1
                                                                    const uint32_t *__restrict__ packed,
                                                                    const _Float16 *__restrict__ scales,
                                                                    const _Float16 *__restrict__ zeros, int N, int K,
-                                                                   _Float16 *__restrict__ out)
+                                                                   _Float16 *__restrict__ out, int ld)
 {
     constexpr int SUB = Fmt<BITS>::SUB;
     constexpr int TILE = tile_dwords<BITS>();
@@ -114,7 +114,7 @@ __global__ __launch_bounds__(64 * NWAVES) void gemv_generic_kernel(const _Float1
                 for (int w = 0; w < NWAVES; ++w)
                     sum += red[w][u * 4 + v][lane];
                 if (n0 + v < N)
-                    out[(size_t)m * N + n0 + v] = (_Float16)sum;
+                    out[(size_t)m * ld + n0 + v] = (_Float16)sum;
             }
         }
     }
@@ -128,7 +128,7 @@ int launch_generic(const void *x, int M, const fq_packed_ref &w, void *out, fq_s
     dim3 grid(Np / Fmt<BITS>::ROWS), block(64 * NWAVES);
     hipLaunchKernelGGL((gemv_generic_kernel<BITS, NWAVES>), grid, block, 0, st, static_cast<const _Float16 *>(x), M,
                        static_cast<const uint32_t *>(w.packed), static_cast<const _Float16 *>(w.scales),
-                       static_cast<const _Float16 *>(w.zeros), w.N, w.K, static_cast<_Float16 *>(out));
+                       static_cast<const _Float16 *>(w.zeros), w.N, w.K, static_cast<_Float16 *>(out), w.ld ? w.ld : w.N);
     return (int)hipGetLastError();
 }
 
@@ -150,6 +150,7 @@ struct GemvJob {
     int N, bits;
     int blk0, nblk; // the workgroups [blk0, blk0 + nblk) of the launch serve this matrix
     int split;      // 2- and 3-bit only: work units are the 16-row sub-blocks of a supertile row, not whole rows
+    int ld;         // elements between consecutive rows of out (N, or more when out is a column range of a wider array)
 };
 
 struct GemvJobs {
@@ -557,7 +558,7 @@ __device__ __forceinline__ void gemv_body(const GemvJob job, int bj, const GemvI
 #pragma unroll
                         for (int w = 0; w < GNW; ++w)
                             sum += rbuf[(w * S * MV + e) * 64 + lane];
-                        job.out[(size_t)mrow * job.N + n] = (_Float16)sum;
+                        job.out[(size_t)mrow * job.ld + n] = (_Float16)sum;
                     }
                 }
                 cur.t = 0;
@@ -798,11 +799,11 @@ int fq_launch_gemv_multi(const fq_gemv_input &src, int M, const fq_packed_ref *w
         const int i = order[k];
         jobs.j[k] = GemvJob{static_cast<const uint32_t *>(w[i].packed), static_cast<const _Float16 *>(w[i].scales),
                             static_cast<const _Float16 *>(w[i].zeros), static_cast<_Float16 *>(outs[i]), w[i].N,
-                            w[i].bits, blk0, nbs[i], parts[i] > 1 ? 1 : 0};
+                            w[i].bits, blk0, nbs[i], parts[i] > 1 ? 1 : 0, w[i].ld ? w[i].ld : w[i].N};
         blk0 += nbs[i];
     }
     for (int i = count; i < 3; ++i)
-        jobs.j[i] = GemvJob{nullptr, nullptr, nullptr, nullptr, 0, 0, blk0, 0, 0};
+        jobs.j[i] = GemvJob{nullptr, nullptr, nullptr, nullptr, 0, 0, blk0, 0, 0, 0};
     const GemvInput in = {static_cast<const _Float16 *>(src.a), static_cast<const _Float16 *>(src.b),
                           static_cast<const _Float16 *>(src.c), static_cast<_Float16 *>(src.aux), src.mode};
     hipLaunchKernelGGL(kernel, dim3(blk0), dim3(64 * GNW), lds, st, in, M, w[0].K, jobs);

@@ -20,6 +20,7 @@ struct fq_packed_ref {
     const void *scales;
     const void *zeros;
     int N, K, bits;
+    int ld = 0; // elements between consecutive rows of the output this matrix writes; 0: N (an output of its own)
 };
 
 // Launchers.  Arguments are validated by the callers in fq_api.hip; each returns a hipError_t as int.

@@ -757,3 +757,54 @@ def test_stream_read_reads_every_word_once(fq, torch):
     assert got == np.bitwise_xor.reduce(host)
     with pytest.raises(fq.FqError):
         fq.fq_stream_read(buf[:3])
+
+
+# ------------------------------------------------- mixed widths within a matrix
+MIXED_CASES = [
+    (384, [(70, 8), (200, 2), (130, 4)]),                              # one launch of three runs, ragged everywhere
+    (256, [(64, 3)]),                                                  # a single run: plain fq_qlinear
+    (1024, [(16, 2), (48, 3), (100, 4), (33, 8), (64, 2)]),            # two launches; odd column offsets (no 8-byte rows)
+    (512, [(128, 4), (128, 2), (256, 8), (128, 3), (64, 4), (64, 2), (32, 8), (224, 3)]),   # the most runs allowed
+]
+
+
+@pytest.mark.parametrize("M", [1, 5, 16, 40, 300])
+@pytest.mark.parametrize("case", MIXED_CASES, ids=lambda c: "K%d_%druns" % (c[0], len(c[1])))
+def test_qlinear_mixed_widths_within_a_matrix(fq, torch, M, case):
+    """A matrix stored as runs of output rows at different bit-widths (Section "Large Language Model
+    Quantization": widths vary within a module too): against the oracle's product with the runs' dequantized
+    rows stacked, at the fq_qlinear tolerance; nothing outside out[M, sum N] written; and column range by
+    column range what fq_qlinear gives for that run alone."""
+    K, runs = case
+    segs, rows = [], []
+    for i, (N, bits) in enumerate(runs):
+        w, codes, s, z = make_matrix(fq, 300 + 7 * i + bits, N, K, bits)
+        segs.append(w)
+        rows.append(oracle.dequant(codes, s, z))
+    X = fq_synth.activations(31, M, K)
+    want = oracle.qlinear(X, np.concatenate(rows, axis=0))
+    total = sum(N for N, _ in runs)
+    out = Guarded(torch, M * total * 2)
+    fq.fq_qlinear_mixed(dev(torch, X), segs, out=out.half(M, total))
+    torch.cuda.synchronize()
+    assert out.intact()
+    y = host16(out.half(M, total))
+    assert qerr(y, want) <= TOL
+    col = 0
+    for w in segs:
+        alone = host16(fq.fq_qlinear(dev(torch, X), w)).astype(np.float64)
+        part = y[:, col:col + w.N].astype(np.float64)
+        assert np.max(np.abs(part - alone)) <= 1e-3 * max(1.0, np.sqrt(np.mean(alone ** 2)))
+        col += w.N
+
+
+def test_qlinear_mixed_rejects_bad_arguments(fq, torch):
+    w, *_ = make_matrix(fq, 1, 64, 128, 4)
+    x = dev(torch, fq_synth.activations(1, 2, 128))
+    with pytest.raises(fq.FqError):
+        fq.fq_qlinear_mixed(x, [w] * 9)
+    with pytest.raises(fq.FqError):
+        fq.fq_qlinear_mixed(x, [])
+    w2, *_ = make_matrix(fq, 2, 64, 256, 4)
+    with pytest.raises(fq.FqError):
+        fq.fq_qlinear_mixed(x, [w, w2])
