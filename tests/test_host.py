@@ -190,3 +190,25 @@ def test_dense_tile_argument_is_validated_on_the_host():
     one = ctypes.c_void_p(16)
     assert fq._lib.fq_dense_f16_tile(one, 4, one, 4, 128, one, 64, None) == -2
     assert "tile_rows" in fq.fq_last_error()
+
+
+def test_new_entry_points_validate_their_arguments_on_the_host():
+    """fq_qlinear_tile, fq_qlinear_mixed and fq_stream_read refuse bad arguments before anything is launched."""
+    import ctypes
+
+    lib = fq._lib
+    assert lib.fq_qlinear_tile(16, 32, 16, 16, 16, 64, 128, 4, 128, 16, 64, None) == -2 and "tile_rows" in fq.fq_last_error()
+    assert lib.fq_qlinear_tile(None, 32, 16, 16, 16, 64, 128, 4, 128, 16, 256, None) == -1
+    seg = (fq._Segment * 2)(fq._Segment(16, 16, 16, 64, 4), fq._Segment(16, 16, 16, 64, 5))
+    p = ctypes.cast(seg, ctypes.c_void_p)
+    assert lib.fq_qlinear_mixed(16, 1, p, 0, 128, 128, 16, None) == -2
+    assert lib.fq_qlinear_mixed(16, 1, p, fq.MAX_SEGMENTS + 1, 128, 128, 16, None) == -2
+    assert lib.fq_qlinear_mixed(16, 1, None, 1, 128, 128, 16, None) == -1
+    assert lib.fq_qlinear_mixed(16, 1, p, 2, 128, 128, 16, None) == -3          # the second run's width
+    assert lib.fq_qlinear_mixed(16, 1, p, 1, 100, 128, 16, None) == -2          # K
+    assert lib.fq_qlinear_mixed(24, 1, p, 1, 128, 128, 16, None) == -5          # alignment of x
+    assert lib.fq_qlinear_mixed(16, 0, p, 1, 128, 128, 16, None) == -2
+    assert lib.fq_stream_read(None, 64, 16, None) == -1
+    assert lib.fq_stream_read(16, 40, 16, None) == -2 and lib.fq_stream_read(16, 0, 16, None) == -2
+    assert lib.fq_stream_read(24, 64, 16, None) == -5
+    assert fq.fq_set_decode_mode(0) in (0, 1)
