@@ -808,3 +808,32 @@ def test_qlinear_mixed_rejects_bad_arguments(fq, torch):
     w2, *_ = make_matrix(fq, 2, 64, 256, 4)
     with pytest.raises(fq.FqError):
         fq.fq_qlinear_mixed(x, [w, w2])
+
+
+def _random_cases(seed, count):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for _ in range(count):
+        M = int(rng.choice([1, 2, 3, 7, 15, 16, 17, 31, 64, 100, 129, 257, 300]))
+        N = int(rng.integers(1, 700))
+        K = 128 * int(rng.integers(1, 13))
+        bits = int(rng.choice(BITS))
+        cases.append((M, N, K, bits))
+    return cases
+
+
+@pytest.mark.parametrize("case", _random_cases(2024, 48), ids=lambda c: "M%d_N%d_K%d_b%d" % c)
+def test_qlinear_on_seeded_random_shapes(fq, torch, case):
+    """Shapes nobody picked by hand: any M around the decode / matrix-core switch and the tile heights, any N
+    (ragged against every supertile height), K from one group to twelve; either kernel family, both tile
+    heights above 16 rows; guard bytes around the output."""
+    M, N, K, bits = case
+    w, codes, s, z = make_matrix(fq, 500 + N + bits, N, K, bits)
+    X = fq_synth.activations(M + K, M, K)
+    want = oracle.qlinear(X, oracle.dequant(codes, s, z))
+    for tile_rows in ((0,) if M <= 16 else (128, 256)):
+        out = Guarded(torch, M * N * 2)
+        fq.fq_qlinear(dev(torch, X), w, out=out.half(M, N), tile_rows=tile_rows)
+        torch.cuda.synchronize()
+        assert out.intact(), tile_rows
+        assert qerr(host16(out.half(M, N)), want) <= TOL, tile_rows
