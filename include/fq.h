@@ -144,9 +144,13 @@ int fq_dequant(const void *packed, const void *scales, const void *zeros,
  * truncating d code bits, Section "Elastic Serving").  For M > 16 the
  * activations (M*K*2 bytes) and the packed weights must each stay below
  * 4 GiB, else FQ_ERR_SHAPE.  Two tile kernels exist for M > 16: 128 activation
- * rows per workgroup (the library's choice: the faster one as measured), and 256
- * rows with K split over two wavefront pairs (each unpacked weight feeds twice as
- * many matrix instructions).  fq_qlinear_tile is the same call with the choice
+ * rows per workgroup, and 256 rows per workgroup of eight wavefronts with the
+ * k-steps of every group split over two wavefront sets (each unpacked weight
+ * feeds twice as many matrix instructions); the library takes the 256-row tiles
+ * once M > 128 and there is a tile for every compute unit, except from 4096 rows
+ * on for 2- and 4-bit matrices wide enough for 128 x 256 tiles (as measured on
+ * MI355X).
+ * fq_qlinear_tile is the same call with the choice
  * made by the caller: tile_rows = 128 or 256 pins a kernel (any M > 16; for tests
  * and tuning; ignored for M <= 16), 0 leaves it to the library; anything else is
  * FQ_ERR_SHAPE.

@@ -171,7 +171,7 @@ extern "C" int fq_qlinear_mixed(const void *x, int M, const fq_segment *segments
         const int n = count - i < 3 ? count - i : 3;
         int e = 0;
         if (M > 16)
-            e = fq_launch_gemm_multi(x, M, &w[i], &outs[i], n, st, 128);
+            e = fq_launch_gemm_multi(x, M, &w[i], &outs[i], n, st);
         else if (stream_all)
             e = fq_launch_gemv_multi(fq_gemv_input{x, nullptr, nullptr, nullptr, 0}, M, &w[i], &outs[i], n, st);
         else

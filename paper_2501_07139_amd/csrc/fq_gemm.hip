@@ -362,22 +362,24 @@ __global__ __launch_bounds__(256, 2) void qgemm_multi_kernel(const _Float16 *__r
 }
 
 // ------------------------------------------------------------ tall tiles
-// 256 activation rows x 128 weight rows per workgroup, for products with many rows.  What bounds the
-// 128-row kernels is not the matrix pipe alone: every wavefront re-reads the whole activation tile from LDS
-// (one 1 KiB operand read per two MFMAs with 32-column wavefront tiles) and unpacks every weight for only 8
-// MFMAs, and LDS reads, vector instructions and MFMAs each fill more than half of their own capacity.  Here a wavefront
-// owns 256 x 64 outputs: one operand read per four MFMAs, one unpacked weight operand per sixteen, and the
-// 256 accumulator registers that takes leave one wavefront per SIMD, whose own instruction stream overlaps
-// loads, unpacking and MFMAs (the operands of the next half group are unpacked between the MFMAs of this one).
-// A 4096-column product at 2048 rows has only 128 tiles of 256 x 256, so the four wavefronts of a workgroup
-// are two column halves times two halves of K: each K half streams its own activation tiles (64 k per step,
-// double buffered, 128 KiB in all) and the two partial sums meet in LDS at the end, in fp32.
-// As measured on MI355X (2048 x 4096 x 4096, 2 bits) this kernel takes 77-80 us against 66-67 us for the
-// 128-row kernel: with one wavefront per SIMD nothing covers the wait for the next step's activation copies
-// (without them 54 us), and LDS has no room for a third buffer.  It is therefore never the library's own
-// choice and runs only when a caller asks for 256-row tiles.
-constexpr int TBM = 256, TBN = 128, TMB = TBM / 16, TNB = 4;
-constexpr int TSLOTS = TBM * 8; // 16-byte slots of one activation tile: 256 rows x 64 k
+// 256 activation rows x 128 weight rows per workgroup of eight wavefronts, one workgroup per CU, for products
+// with many rows.  In the 128-row kernels every unpacked weight operand feeds 8 MFMAs and the unpacking is the
+// largest share of what a wavefront issues beside its MFMAs; here a wavefront owns 256 x 32 outputs (128
+// accumulator registers), so an operand feeds 16.  A 4096-column product at 2048 rows has only 256 such tiles,
+// one per CU, so the second wavefront of every SIMD comes from splitting K inside the workgroup: wavefront
+// (kh, nq) multiplies k-steps 2*kh and 2*kh+1 of every group with the weight rows 32*nq..+31, loads only that
+// half of a chunk and unpacks only its eight pairs; the two partial sums meet in LDS at the end, in fp32.
+// The loop is the narrow tiles' software pipeline (loads two groups ahead, operands of the next group
+// unpacked ahead of this group's MFMAs in program order, one barrier per group).
+//
+// The two activation buffers are two LDS arrays on purpose.  A kernel with more than one LDS object has its LDS
+// accesses tagged with alias scopes, and the compiler then waits for every direct-to-LDS load in flight before
+// a read that may touch the same object: with both buffers in one array the reads of one buffer wait for the
+// copies into the other right after they were issued, and the copy's whole latency (0.6 us per group here)
+// lands on the wavefront.  With separate arrays, selected at compile time, the copies stay in flight until the
+// wait at the end of the iteration.  As measured on MI355X (2048 rows, 4096 x 4096 and 4096 x 11008, same
+// harness): 6-13 % faster than the 128-row kernels at every bit-width.
+constexpr int TBM = 256, TBN = 128, TMB = TBM / 16, TNB = 2;
 
 // biased pair P of a chunk (elements 2v, 2v+1 of k-step P/4, v = P%4) and the class of its bit position;
 // the same fields and constants as unpack_dequant, one pair at a time
@@ -432,29 +434,6 @@ __device__ __forceinline__ uint32_t biased_pair(const uint32_t (&C)[BITS], const
 template <int BITS, int P>
 constexpr int pair_class() { return (BITS == 3 && P == 15) ? 0 : PairAt<BITS, P>::CLS; }
 
-// (code - zero) * scale for pair P of a chunk, as the two fp16 numbers of one operand register, one
-// instruction per stage so that the caller can place the stages of two pairs alternately (a packed fp16
-// instruction that reads the previous one's result costs a wait state).  The arithmetic is unpack_dequant's:
-// stage 0 biased field, then + (bias - zero), * scale with integer zeros (bias + zero is exact, an integer
-// below 2048), else + bias, - zero, * scale.  `live` false (a step past the end of this wavefront's share of
-// K) gives zeros.  The per-chunk terms are written out at every call; calls on the same chunk share them.
-template <int BITS, bool INTZ, int P, int STAGE>
-__device__ __forceinline__ uint32_t unpack_stage(uint32_t t, const WChunk<BITS> &w, bool live, const UnpackConsts<BITS> &uc)
-{
-    constexpr int CLS = pair_class<BITS, P>();
-    if constexpr (STAGE == 0) {
-        return biased_pair<BITS, P>(w.c, uc);
-    } else {
-        const h2 zero2 = as_h2(w.zero * 0x10001u), scale2 = as_h2((live ? w.scale : 0u) * 0x10001u);
-        if constexpr (INTZ)
-            return as_u32(STAGE == 1 ? as_h2(t) + (uc.mb[CLS] - zero2) : as_h2(t) * scale2);
-        else
-            return as_u32(STAGE == 1 ? as_h2(t) + uc.mb[CLS] : STAGE == 2 ? as_h2(t) - zero2 : as_h2(t) * scale2);
-    }
-}
-template <bool INTZ>
-constexpr int unpack_stages() { return INTZ ? 3 : 4; }
-
 template <int... I, class F>
 __device__ __forceinline__ void static_for_impl(F &&f, std::integer_sequence<int, I...>)
 {
@@ -467,38 +446,72 @@ __device__ __forceinline__ void static_for(F &&f)
     static_for_impl(static_cast<F &&>(f), std::make_integer_sequence<int, N>{});
 }
 
-// c += a . b with the accumulator held in place in an accumulator register.  Written as an instruction
-// because the compiler, left to allocate 256 accumulator registers itself, moves them between register
-// files around every MFMA.  The compiler does not know what this instruction is, so no result of it may be
-// read by anything but another mfma_acc on the same accumulator before settle_mfma().
-__device__ __forceinline__ void mfma_acc(f4 &c, h8 a, h8 b)
+// The dwords of a chunk that hold k-steps 2*KH and 2*KH+1 (3 bits: all three, the last pair's bits sit on
+// top of every dword), with the row's scale and zero; the other entries of w.c stay unset and unread.
+template <int BITS, int KH>
+__device__ __forceinline__ void load_whalf(WChunk<BITS> &w, const GemmBuffers &buf, int rb16, int Np16, int G, int g,
+                                           int lane)
 {
-    asm("v_mfma_f32_16x16x32_f16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
+    constexpr int SUB = Fmt<BITS>::SUB;
+    const int rb = min(rb16, Np16 - 1); // blocks past the end re-read the last block (see load_wchunk)
+    const uint32_t tile_off = (uint32_t)((rb / SUB) * G + g) * (uint32_t)(tile_dwords<BITS>() * 4);
+    const int u = rb % SUB;
+    const uint32_t lo = (uint32_t)lane * 16u;
+    if constexpr (BITS == 2) {
+        w.c[KH] = buf_load_b32(buf.packed, lo + 8u * (uint32_t)u + 4u * KH, tile_off);
+    } else if constexpr (BITS == 4) {
+        const u2v v = buf_load_b64(buf.packed, lo + 8u * KH, tile_off);
+        w.c[2 * KH] = v.x; w.c[2 * KH + 1] = v.y;
+    } else if constexpr (BITS == 8) {
+        const u4v v = buf_load_b128(buf.packed, lo + 1024u * KH, tile_off);
+        w.c[4 * KH] = v.x; w.c[4 * KH + 1] = v.y; w.c[4 * KH + 2] = v.z; w.c[4 * KH + 3] = v.w;
+    } else {
+        buf_load_chunk<BITS>(buf.packed, tile_off, u, lane, w.c);
+    }
+    const uint32_t meta_off = (uint32_t)(rb * G + g) * 32u, mlo = (uint32_t)(lane & 15) * 2u;
+    w.scale = buf_load_u16(buf.scales, mlo, meta_off);
+    w.zero = buf_load_u16(buf.zeros, mlo, meta_off);
 }
-// the wait states between the last MFMA and the first other read of its result (at most 18 for this shape)
-__device__ __forceinline__ void settle_mfma() { asm volatile("s_nop 15\n\ts_nop 15" ::: "memory"); }
 
-__device__ __forceinline__ int tall_slot(int row, int ch) { return row * 8 + (ch ^ ((row >> 1) & 7)); }
+// Operands of k-steps 2*KH and 2*KH+1 of a chunk: (code - zero) * scale per weight in packed fp16, the
+// arithmetic of unpack_dequant pair by pair (integer zeros: bias and zero leave in one exact addition).
+template <int BITS, bool INTZ, int KH>
+__device__ __forceinline__ void unpack_khalf(const WChunk<BITS> &w, const UnpackConsts<BITS> &uc, h8 (&a)[2])
+{
+    const h2 zero2 = as_h2(w.zero * 0x10001u), scale2 = as_h2(w.scale * 0x10001u);
+    static_for<2>([&](auto s_tag) {
+        constexpr int s = decltype(s_tag)::value;
+        h2 q[4];
+        static_for<4>([&](auto v_tag) {
+            constexpr int v = decltype(v_tag)::value, P = 4 * (2 * KH + s) + v, CLS = pair_class<BITS, P>();
+            const h2 b = as_h2(biased_pair<BITS, P>(w.c, uc));
+            if constexpr (INTZ)
+                q[v] = (b + (uc.mb[CLS] - zero2)) * scale2;
+            else
+                q[v] = ((b + uc.mb[CLS]) - zero2) * scale2;
+        });
+        a[s] = make_h8(q[0], q[1], q[2], q[3]);
+    });
+}
 
-// One 256 x 128 output tile.  Xs: [K half][buffer][TSLOTS]; after the loop the same memory carries the
-// second K half's partial sums to the first.
+// One 256 x 128 output tile.  Xs0, Xs1: the two activation tiles (256 rows x 128 k each, laid out like the
+// narrow tiles'); after the loop the same memory carries the second K half's partial sums to the first.
 template <int BITS>
-__device__ __forceinline__ void qgemm_tall_tile(h8 (*Xs)[2][TSLOTS], const _Float16 *__restrict__ x, int M,
+__device__ __forceinline__ void qgemm_tall_tile(h8 *Xs0, h8 *Xs1, const _Float16 *__restrict__ x, int M,
                                                 const uint32_t *__restrict__ packed,
                                                 const _Float16 *__restrict__ scales,
                                                 const _Float16 *__restrict__ zeros, int N, int K,
-                                                _Float16 *__restrict__ out, int tile)
+                                                _Float16 *__restrict__ out, int ld, int tile)
 {
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int kh = wave >> 1, nw = wave & 1; // half of K, half of the tile's weight rows
+    const int kh = wave >> 2, nq = wave & 3; // half of every group's k-steps, quarter of the tile's weight rows
     const int NT = (N + TBN - 1) / TBN, MT = (M + TBM - 1) / TBM;
     const int band = tile / (4 * NT), rest = tile - band * 4 * NT, height = min(4, MT - 4 * band);
     const int m0 = (4 * band + rest % height) * TBM, n0 = (rest / height) * TBN;
-    const int G = K >> 7, Gh = (G + 1) >> 1;
-    const int g0 = kh * Gh, gcount = min(G - g0, Gh); // this half's groups; the other half runs as many steps
+    const int G = K >> 7;
     const int Np16 = ((N + 63) / 64 * 64) >> 4;
-    const int rb0 = (n0 >> 4) + nw * TNB;
+    const int rb0 = (n0 >> 4) + nq * TNB;
 
     GemmBuffers buf;
     buf.x = make_rsrc(x, (uint32_t)M * (uint32_t)K * 2u);
@@ -507,21 +520,12 @@ __device__ __forceinline__ void qgemm_tall_tile(h8 (*Xs)[2][TSLOTS], const _Floa
     buf.scales = make_rsrc(scales, Np * (uint32_t)G * 2u);
     buf.zeros = make_rsrc(zeros, Np * (uint32_t)G * 2u);
 
-    // Activation copies: a K half's tile (256 rows x 64 k) is filled by its two wavefronts, 16 copies of 1 KiB
-    // each; copy i of a wavefront fills the slots of rows 128*nw + 8*i + lane/8, position lane%8, which holds
-    // chunk position ^ (row/2)%8.  Rows past M re-read row M-1.
-    uint32_t xoff[16];
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        const int row = 128 * nw + 8 * i + (lane >> 3), ch = (lane & 7) ^ ((row >> 1) & 7);
-        xoff[i] = ((uint32_t)min(m0 + row, M - 1) * (uint32_t)K + (uint32_t)ch * 8u) * 2u;
-    }
-    auto copy_x = [&](int buffer, int step) { // step of this half: group g0 + step/2, k-steps 2*(step%2)..+1
-        const uint32_t koff = (uint32_t)min(g0 + (step >> 1), G - 1) * 256u + (uint32_t)(step & 1) * 128u;
-#pragma unroll
-        for (int i = 0; i < 16; ++i)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(buf.x, &Xs[kh][buffer][(128 * nw + 8 * i) * 8], 16, xoff[i], koff, 0, 0);
-    };
+    // Activation copies, global memory straight into LDS: copy i of a wavefront fills the 64 slots from
+    // 64*wave + 512*i, i.e. rows 4*wave + 32*i + lane/16; slot (row, pos) holds chunk pos ^ (row & 15).  Rows
+    // past M lie past the descriptor's size and read as zero; their results are never stored.
+    const int xrow = 4 * wave + (lane >> 4), xch = (lane & 15) ^ (xrow & 15);
+    const uint32_t xoff0 = ((uint32_t)(m0 + xrow) * (uint32_t)K + (uint32_t)xch * 8u) * 2u;
+    const uint32_t xstep = 64u * (uint32_t)K; // 32 rows
 
     f4 acc[TNB][TMB];
 #pragma unroll
@@ -530,158 +534,125 @@ __device__ __forceinline__ void qgemm_tall_tile(h8 (*Xs)[2][TSLOTS], const _Floa
         for (int j = 0; j < TMB; ++j)
             acc[i][j] = f4{0.f, 0.f, 0.f, 0.f};
 
-    WChunk<BITS> wcur[TNB], wnext[TNB];
-    auto load_group = [&](WChunk<BITS> (&w)[TNB], int gl) {
 #pragma unroll
-        for (int i = 0; i < TNB; ++i)
-            load_wchunk<BITS>(w[i], buf, rb0 + i, Np16, G, K, min(g0 + gl, G - 1), lane);
-    };
-    copy_x(0, 0);
-    load_group(wcur, 0);
-    __builtin_amdgcn_s_waitcnt(FQ_WAIT_VMCNT0);
-    __syncthreads();
+    for (int i = 0; i < 8; ++i)
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(buf.x, &Xs0[64 * wave + 512 * i], 16, xoff0, xstep * i, 0, 0);
 
     // integer zeros: one addition takes bias and zero away (see qgemm_tile)
     bool intz;
     {
         const uint32_t first = (uint32_t)(n0 >> 4) * (uint32_t)G * 16u, count = (TBN / 16) * (uint32_t)G * 16u;
         int frac = 0;
-        for (uint32_t i = (uint32_t)tid * 8u; i < count; i += 256u * 8u) {
+        for (uint32_t i = (uint32_t)tid * 8u; i < count; i += 512u * 8u) { // past the array: zeros
             const h8 z = __builtin_bit_cast(h8, buf_load_b128(buf.zeros, (first + i) * 2u, 0));
 #pragma unroll
             for (int e = 0; e < 8; ++e)
                 frac |= z[e] != __builtin_truncf16(z[e]);
         }
-        intz = !__syncthreads_or(frac);
+        __builtin_amdgcn_s_waitcnt(FQ_WAIT_VMCNT0); // the first activation tile has landed ...
+        intz = !__syncthreads_or(frac);             // ... in every wavefront
     }
 
     UnpackConsts<BITS> uc;
     uc.init();
-    const int brow = lane & 15, bsw = (brow >> 1) & 7;
-    const int bslot0 = brow * 8 + ((lane >> 4) ^ bsw), bslot1 = brow * 8 + ((4 + (lane >> 4)) ^ bsw);
+    const int brow = lane & 15;
 
-    // A step (64 k) is eight sections of 16 MFMAs: section sec multiplies k-step sec/4 of the step with the four
-    // activation row blocks 4*(sec%4)..+3.  The wavefront is alone on its SIMD, so its own instruction order is
-    // the overlap: every MFMA is preceded by a few instructions of other work that issue while the previous
-    // MFMA occupies the pipe (four issue slots each), and nothing moves between these slots.  Per section: the
-    // four operand reads of the next section (two sets of registers), one operand register of the next step
-    // unpacked per four MFMAs; the copies of the next step's activations go out over the first two sections
-    // and the next group's weight loads in the third, so that they have most of a step to land; the barrier
-    // sits ahead of the last section's MFMAs, which cover the first reads of the next step.
-    auto main_loop = [&](auto intz_tag) {
+    auto main_loop = [&](auto intz_tag, auto kh_tag) {
         constexpr bool INTZ = decltype(intz_tag)::value;
-        u4v ap[TNB][2], aq[TNB][2]; // operands as four registers of one pair each
-        h8 b[2][4];
-        auto read_b = [&](h8 &dst, int buffer, int sec, int jj) {
-            dst = Xs[kh][buffer][((sec >> 2) ? bslot1 : bslot0) + ((sec & 3) * 4 + jj) * 128];
-        };
-        auto step = [&](int buffer, int next_step, u4v (&ac)[TNB][2], auto other_work) {
-            const uint32_t koff = (uint32_t)min(g0 + (next_step >> 1), G - 1) * 256u + (uint32_t)(next_step & 1) * 128u;
-            static_for<8>([&](auto sec_tag) {
-                constexpr int sec = decltype(sec_tag)::value;
-                if constexpr (sec == 7) {
-                    __builtin_amdgcn_s_waitcnt(0x0070); // vmcnt(0), lgkmcnt(0): copies, weights, operand reads
-                    __syncthreads();                    // the other buffer is complete, this one is free
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-                static_for<16>([&](auto m_tag) {
-                    constexpr int m = decltype(m_tag)::value, jj = m >> 2, i = m & 3;
-                    if constexpr (m < 4) {
-                        if constexpr (sec < 7)
-                            read_b(b[(sec + 1) & 1][m], buffer, sec + 1, m);
-                        else
-                            read_b(b[0][m], buffer ^ 1, 0, m);
-                    }
-                    if constexpr (sec < 2 && (m & 1) == 0) { // copy 8*sec + m/2 of the next step's activations
-                        constexpr int c = 8 * sec + m / 2;
-                        __builtin_amdgcn_raw_ptr_buffer_load_lds(buf.x, &Xs[kh][buffer ^ 1][(128 * nw + 8 * c) * 8], 16,
-                                                                 xoff[c], koff, 0, 0);
-                    }
-                    other_work(sec_tag, m_tag);
-                    mfma_acc(acc[i][(sec & 3) * 4 + jj], __builtin_bit_cast(h8, ac[i][sec >> 2]), b[sec & 1][jj]);
-                    __builtin_amdgcn_sched_barrier(0);
-                });
-            });
-        };
-        // the next step's operand of this section (chunk sec/2, k-step KS0 + sec%2): pairs 0,1 in slots 4.., pairs
-        // 2,3 in slots 8.., one stage of both pairs per slot
-        uint32_t st[2];
-        auto unpack_slot = [&](auto ks_tag, auto m_tag, const WChunk<BITS> &w, bool live, u4v &dst) {
-            constexpr int KS = decltype(ks_tag)::value, m = decltype(m_tag)::value, NST = unpack_stages<INTZ>();
-            constexpr int duo = (m >> 2) - 1, stage = m & 3;
-            if constexpr ((duo == 0 || duo == 1) && stage < NST) {
-                constexpr int P = 4 * KS + 2 * duo;
-                st[0] = unpack_stage<BITS, INTZ, P, stage>(st[0], w, live, uc);
-                st[1] = unpack_stage<BITS, INTZ, P + 1, stage>(st[1], w, live, uc);
-                if constexpr (stage == NST - 1) {
-                    dst[2 * duo] = st[0];
-                    dst[2 * duo + 1] = st[1];
-                }
-            }
-        };
-        static_for<TNB>([&](auto i_tag) {
-            constexpr int i = decltype(i_tag)::value;
-            static_for<2>([&](auto ks_tag) {
-                static_for<8>([&](auto m8_tag) {
-                    unpack_slot(ks_tag, std::integral_constant<int, 4 + decltype(m8_tag)::value>{}, wcur[i], gcount > 0,
-                                ap[i][decltype(ks_tag)::value]);
-                });
-            });
-        });
-#pragma unroll
-        for (int jj = 0; jj < 4; ++jj)
-            read_b(b[0][jj], 0, 0, jj);
-        for (int gl = 0; gl < Gh; ++gl) {
-            // first half of the group; meanwhile k-steps 2 and 3 of this group's chunks become operands, and
-            // the next group's chunks are requested
-            step(0, 2 * gl + 1, ap, [&](auto sec_tag, auto m_tag) {
-                constexpr int sec = decltype(sec_tag)::value, m = decltype(m_tag)::value;
-                if constexpr (sec == 2 && (m & 3) == 0)
-                    load_wchunk<BITS>(wnext[m >> 2], buf, rb0 + (m >> 2), Np16, G, K, min(g0 + gl + 1, G - 1), lane);
-                unpack_slot(std::integral_constant<int, 2 + (sec & 1)>{}, m_tag, wcur[sec >> 1], gl < gcount,
-                            aq[sec >> 1][sec & 1]);
-            });
-            // second half; k-steps 0 and 1 of the next group's chunks become operands
-            step(1, 2 * gl + 2, aq, [&](auto sec_tag, auto m_tag) {
-                constexpr int sec = decltype(sec_tag)::value;
-                unpack_slot(std::integral_constant<int, (sec & 1)>{}, m_tag, wnext[sec >> 1], gl + 1 < gcount,
-                            ap[sec >> 1][sec & 1]);
-            });
+        constexpr int KH = decltype(kh_tag)::value;
+        WChunk<BITS> wc[TNB], wd[TNB];
+        h8 a0[TNB][2], a1[TNB][2];
+        auto unpack_all = [&](WChunk<BITS> (&w)[TNB], h8 (&a)[TNB][2]) {
 #pragma unroll
             for (int i = 0; i < TNB; ++i)
-                wcur[i] = wnext[i];
+                unpack_khalf<BITS, INTZ, KH>(w[i], uc, a[i]);
+        };
+        auto load_all = [&](WChunk<BITS> (&w)[TNB], int g) {
+#pragma unroll
+            for (int i = 0; i < TNB; ++i)
+                load_whalf<BITS, KH>(w[i], buf, rb0 + i, Np16, G, min(g, G - 1), lane);
+        };
+        // Xc: this group's activations, Xn: the buffer the next group's are copied into.  Past the last group
+        // both prefetches repeat it (nobody reads them): no branch in the iteration.
+        auto body = [&](h8 *Xc, h8 *Xn, int g, h8 (&ac)[TNB][2], h8 (&an)[TNB][2], WChunk<BITS> (&wn)[TNB],
+                        WChunk<BITS> (&wl)[TNB]) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(buf.x, &Xn[64 * wave + 512 * i], 16, xoff0,
+                                                         (uint32_t)min(g + 1, G - 1) * 256u + xstep * i, 0, 0);
+            __builtin_amdgcn_sched_barrier(0); // the copies go out first: they have the whole iteration to land
+            load_all(wl, g + 2);
+            unpack_all(wn, an); // ahead of the MFMAs in program order: the scheduler fills their shadows with it
+#pragma unroll
+            for (int s = 0; s < 2; ++s) {
+#pragma unroll
+                for (int jh = 0; jh < TMB; jh += 8) {
+                    h8 b[8];
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) {
+                        const int ch = 4 * (2 * KH + s) + (lane >> 4);
+                        b[j] = Xc[((jh + j) * 16 + brow) * 16 + (ch ^ brow)];
+                    }
+#pragma unroll
+                    for (int i = 0; i < TNB; ++i)
+#pragma unroll
+                        for (int j = 0; j < 8; ++j)
+                            acc[i][jh + j] = mfma16x16x32(ac[i][s], b[j], acc[i][jh + j]);
+                }
+            }
+            __builtin_amdgcn_s_waitcnt(FQ_WAIT_VMCNT0); // this wavefront's copies into Xn have landed ...
+            __syncthreads();                            // ... and everybody's; Xc is free
+            __builtin_amdgcn_sched_barrier(0);          // nothing moves from one iteration into the other
+        };
+        load_all(wc, 0);
+        unpack_all(wc, a0);
+        load_all(wc, 1);
+        int g = 0;
+        for (; g + 1 < G; g += 2) {
+            body(Xs0, Xs1, g, a0, a1, wc, wd);
+            body(Xs1, Xs0, g + 1, a1, a0, wd, wc);
         }
+        if (g < G)
+            body(Xs0, Xs1, g, a0, a1, wc, wd);
     };
-    if (intz)
-        main_loop(std::true_type{});
-    else
-        main_loop(std::false_type{});
+    if (kh == 0) {
+        if (intz)
+            main_loop(std::true_type{}, std::integral_constant<int, 0>{});
+        else
+            main_loop(std::false_type{}, std::integral_constant<int, 0>{});
+    } else {
+        if (intz)
+            main_loop(std::true_type{}, std::integral_constant<int, 1>{});
+        else
+            main_loop(std::false_type{}, std::integral_constant<int, 1>{});
+    }
 
-    settle_mfma();
-    // the second K half hands its sums over: block (i, j) of column half nw at float4 ((nw*64 + i*16 + j)*64 + lane)
-    f4 *red = reinterpret_cast<f4 *>(&Xs[0][0][0]);
+    // The second K half hands its sums over (every iteration ended with a wait for all loads and a barrier, so
+    // both arrays are free): block (i, j) of column quarter nq at float4 (nq*16 + j)*64 + lane of array i.
+    f4 *red0 = reinterpret_cast<f4 *>(Xs0), *red1 = reinterpret_cast<f4 *>(Xs1);
     if (kh == 1) {
 #pragma unroll
-        for (int i = 0; i < TNB; ++i)
-#pragma unroll
-            for (int j = 0; j < TMB; ++j)
-                red[((nw * 64 + i * 16 + j) << 6) + lane] = acc[i][j];
+        for (int j = 0; j < TMB; ++j) {
+            red0[((nq * 16 + j) << 6) + lane] = acc[0][j];
+            red1[((nq * 16 + j) << 6) + lane] = acc[1][j];
+        }
     }
     __syncthreads();
     if (kh == 1)
         return;
-    // store: lane holds m = lane%16 and n = 4*(lane/16) + v of each 16x16 block
+    // store: lane holds m = lane%16 and n = 4*(lane/16) + v of each 16x16 block (see qgemm_tile)
+    const bool vec_ok = (ld & 3) == 0 && (reinterpret_cast<uintptr_t>(out) & 7) == 0;
 #pragma unroll
     for (int j = 0; j < TMB; ++j) {
         const int m = m0 + j * 16 + (lane & 15);
 #pragma unroll
         for (int i = 0; i < TNB; ++i) {
-            const f4 r = acc[i][j] + red[((nw * 64 + i * 16 + j) << 6) + lane];
+            const f4 r = acc[i][j] + (i ? red1 : red0)[((nq * 16 + j) << 6) + lane];
             const int n = (rb0 + i) * 16 + 4 * (lane >> 4);
             if (m >= M)
                 continue;
-            _Float16 *o = out + (size_t)m * N + n;
-            if (n + 3 < N && (N & 3) == 0) {
+            _Float16 *o = out + (size_t)m * ld + n;
+            if (n + 3 < N && vec_ok) {
                 h4 v = {(_Float16)r[0], (_Float16)r[1], (_Float16)r[2], (_Float16)r[3]};
                 *reinterpret_cast<h4 *>(o) = v;
             } else {
@@ -698,17 +669,18 @@ struct TallJob {
     const uint32_t *packed;
     const _Float16 *scales, *zeros;
     _Float16 *out;
-    int N, bits, tile0;
+    int N, bits, tile0, ld;
 };
 struct TallJobs {
     TallJob j[3];
     int count, total;
 };
 
-// One wavefront per SIMD: the whole register file (256 vector + 256 accumulator registers) belongs to it.
-__global__ __launch_bounds__(256, 1) void qgemm_tall_kernel(const _Float16 *__restrict__ x, int M, int K, TallJobs jobs)
+// Eight wavefronts of 256 registers each: one workgroup per CU, two wavefronts per SIMD.
+__global__ __launch_bounds__(512, 1) void qgemm_tall_kernel(const _Float16 *__restrict__ x, int M, int K, TallJobs jobs)
 {
-    __shared__ h8 Xs[2][2][TSLOTS];
+    __shared__ h8 Xs0[TBM * 16];
+    __shared__ h8 Xs1[TBM * 16];
     int tile = xcd_tile(jobs.total);
     if (tile < 0)
         return;
@@ -720,10 +692,10 @@ __global__ __launch_bounds__(256, 1) void qgemm_tall_kernel(const _Float16 *__re
     const TallJob job = ji == 0 ? jobs.j[0] : (ji == 1 ? jobs.j[1] : jobs.j[2]);
     tile -= job.tile0;
     switch (job.bits) {
-    case 2: qgemm_tall_tile<2>(Xs, x, M, job.packed, job.scales, job.zeros, job.N, K, job.out, tile); break;
-    case 3: qgemm_tall_tile<3>(Xs, x, M, job.packed, job.scales, job.zeros, job.N, K, job.out, tile); break;
-    case 4: qgemm_tall_tile<4>(Xs, x, M, job.packed, job.scales, job.zeros, job.N, K, job.out, tile); break;
-    default: qgemm_tall_tile<8>(Xs, x, M, job.packed, job.scales, job.zeros, job.N, K, job.out, tile); break;
+    case 2: qgemm_tall_tile<2>(Xs0, Xs1, x, M, job.packed, job.scales, job.zeros, job.N, K, job.out, job.ld, tile); break;
+    case 3: qgemm_tall_tile<3>(Xs0, Xs1, x, M, job.packed, job.scales, job.zeros, job.N, K, job.out, job.ld, tile); break;
+    case 4: qgemm_tall_tile<4>(Xs0, Xs1, x, M, job.packed, job.scales, job.zeros, job.N, K, job.out, job.ld, tile); break;
+    default: qgemm_tall_tile<8>(Xs0, Xs1, x, M, job.packed, job.scales, job.zeros, job.N, K, job.out, job.ld, tile); break;
     }
 }
 
@@ -733,6 +705,23 @@ int wide_tiles_pay(int M, int N)
 {
     const long tiles = (long)((N + 255) / 256) * ((M + QBM - 1) / QBM);
     return tiles >= 2 * 256;
+}
+
+int tall_tiles(int M, int N) { return ((N + TBN - 1) / TBN) * ((M + TBM - 1) / TBM); }
+
+// Tile height for a launch of `count` matrices.  A tall tile occupies a whole CU, so tall tiles pay once there is
+// one for every CU and the rows fill more than half of a tile: as measured, 3-14 % faster than the 128-row tiles
+// at 2048 rows at every bit-width.  From 4096 rows on, the 128 x 256 tiles of 2- and 4-bit matrices run several
+// full rounds and are level or 2-6 % ahead, so launches made of such matrices only stay with them.
+int choose_tile_rows(int M, const fq_packed_ref *w, int count)
+{
+    long tall = 0;
+    bool all_wide = M >= 4096;
+    for (int i = 0; i < count; ++i) {
+        tall += tall_tiles(M, w[i].N);
+        all_wide = all_wide && (w[i].bits == 2 || w[i].bits == 4) && wide_tiles_pay(M, w[i].N);
+    }
+    return (M > 128 && tall >= 256 && !all_wide) ? 256 : 128;
 }
 
 template <int BITS, int QNB>
@@ -764,20 +753,17 @@ static bool fits_32bit(size_t a, size_t b, size_t elem_bytes) { return a * b * e
 
 static int launch_tall(const void *x, int M, const fq_packed_ref *w, void *const *outs, int count, fq_stream st)
 {
-    for (int i = 0; i < count; ++i)
-        if (w[i].ld && w[i].ld != w[i].N)
-            return (int)hipErrorInvalidValue; // this kernel writes outputs of their own only
     TallJobs jobs;
     jobs.count = count;
     int total = 0;
     for (int i = 0; i < count; ++i) {
         jobs.j[i] = TallJob{static_cast<const uint32_t *>(w[i].packed), static_cast<const _Float16 *>(w[i].scales),
                             static_cast<const _Float16 *>(w[i].zeros), static_cast<_Float16 *>(outs[i]), w[i].N,
-                            w[i].bits, total};
-        total += ((w[i].N + TBN - 1) / TBN) * ((M + TBM - 1) / TBM);
+                            w[i].bits, total, w[i].ld ? w[i].ld : w[i].N};
+        total += tall_tiles(M, w[i].N);
     }
     jobs.total = total;
-    hipLaunchKernelGGL(qgemm_tall_kernel, dim3(8 * ((total + 7) / 8)), dim3(256), 0, st,
+    hipLaunchKernelGGL(qgemm_tall_kernel, dim3(8 * ((total + 7) / 8)), dim3(512), 0, st,
                        static_cast<const _Float16 *>(x), M, w[0].K, jobs);
     return (int)hipGetLastError();
 }
@@ -787,7 +773,9 @@ int fq_launch_gemm(const void *x, int M, const fq_packed_ref &w, void *out, fq_s
     const size_t Np = ((size_t)w.N + 63) / 64 * 64;
     if (!fits_32bit(M, w.K, 2) || Np / 8 * w.K * w.bits >= ((size_t)1 << 32))
         return (int)hipErrorInvalidValue;
-    if (tile_rows == 256) // never the library's own choice: as measured the 128-row kernels are faster
+    if (tile_rows == 0)
+        tile_rows = choose_tile_rows(M, &w, 1);
+    if (tile_rows == 256)
         return launch_tall(x, M, &w, &out, 1, st);
     if (w.ld && w.ld != w.N) // a column range of a wider output: the multi-matrix kernel carries the row pitch
         return fq_launch_gemm_multi(x, M, &w, &out, 1, st, 128);
@@ -810,6 +798,8 @@ int fq_launch_gemm_multi(const void *x, int M, const fq_packed_ref *w, void *con
         if (w[i].K != w[0].K || !fits_32bit(M, w[i].K, 2) || Np / 8 * w[i].K * w[i].bits >= ((size_t)1 << 32))
             return (int)hipErrorInvalidValue;
     }
+    if (tile_rows == 0)
+        tile_rows = choose_tile_rows(M, w, count);
     if (tile_rows == 256)
         return launch_tall(x, M, w, outs, count, st);
     GemmJobs jobs;
