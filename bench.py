@@ -52,7 +52,7 @@ SEED = 1
 # WRITE_SIZE, KiB per dispatch) scaled by what the same counters read for a 64 MiB device copy (FETCH_SIZE
 # reads 0.500 of the true bytes on this machine, WRITE_SIZE 1.000).  Valid only for the kernel sources whose
 # digest is recorded with it; bench.py reports null once they have changed.
-GEMM_TRAFFIC = {"kernel_digest": "b8f7367003a5db6c", "fetch_bytes": 805.2e6, "write_bytes": 174.1e6}  # profiles/qgemm_gemv_llama2-7b-block_hbm_traffic.txt
+GEMM_TRAFFIC = {"kernel_digest": "6028a6ce06b7470a", "fetch_bytes": 820.2e6, "write_bytes": 174.1e6}  # profiles/qgemm_gemv_llama2-7b-block_hbm_traffic.txt
 
 
 SWAP_ENTRY = 4  # the matrix (gate) the transition leg swaps
@@ -636,7 +636,7 @@ def main():
         "kernels": {"gemm": kernels, "gemv": gemv_kernels},
         "roofline": {"bound": "mfma", "achieved": round(gemm_tflops, 1), "peak": PEAK_MFMA_F16_TFLOPS,
                      "unit": "TFLOP/s", "frac": round(gemm_tflops / PEAK_MFMA_F16_TFLOPS, 4), "traffic": traffic,
-                     "kernel": "qgemm_kernel (dequant-GEMM, M=2048, the 7 launches of the block)",
+                     "kernel": "qgemm_tall_kernel (dequant-GEMM, M=2048, the 7 launches of the block, 256-row tiles)",
                      "algorithmic_flops": gemm_flops, "algorithmic_bytes": gemm_alg_bytes},
         "roofline_gemv": {"bound": "hbm", "achieved": round(gemv_bytes / ms_dec / 1e6, 1), "peak": PEAK_HBM_GBPS,
                           "unit": "GB/s", "frac": round(gemv_bytes / ms_dec / 1e6 / PEAK_HBM_GBPS, 4),

@@ -506,9 +506,11 @@ __device__ __forceinline__ void qgemm_tall_tile(h8 *Xs0, h8 *Xs1, const _Float16
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int kh = wave >> 2, nq = wave & 3; // half of every group's k-steps, quarter of the tile's weight rows
+    // tiles are numbered in bands of two activation row-tiles (row-tile fastest): the 32 tiles an XCD holds at a
+    // time share 512 activation rows (4 MiB at k = 4096, the size of its L2) and 16 weight tiles
     const int NT = (N + TBN - 1) / TBN, MT = (M + TBM - 1) / TBM;
-    const int band = tile / (4 * NT), rest = tile - band * 4 * NT, height = min(4, MT - 4 * band);
-    const int m0 = (4 * band + rest % height) * TBM, n0 = (rest / height) * TBN;
+    const int band = tile / (2 * NT), rest = tile - band * 2 * NT, height = min(2, MT - 2 * band);
+    const int m0 = (2 * band + rest % height) * TBM, n0 = (rest / height) * TBN;
     const int G = K >> 7;
     const int Np16 = ((N + 63) / 64 * 64) >> 4;
     const int rb0 = (n0 >> 4) + nq * TNB;
@@ -583,20 +585,21 @@ __device__ __forceinline__ void qgemm_tall_tile(h8 *Xs0, h8 *Xs1, const _Float16
             __builtin_amdgcn_sched_barrier(0); // the copies go out first: they have the whole iteration to land
             load_all(wl, g + 2);
             unpack_all(wn, an); // ahead of the MFMAs in program order: the scheduler fills their shadows with it
+            constexpr int JB = BITS == 3 ? 4 : 8; // operand reads per batch (3 bits: the fewest registers to spare)
 #pragma unroll
             for (int s = 0; s < 2; ++s) {
 #pragma unroll
-                for (int jh = 0; jh < TMB; jh += 8) {
-                    h8 b[8];
+                for (int jh = 0; jh < TMB; jh += JB) {
+                    h8 b[JB];
 #pragma unroll
-                    for (int j = 0; j < 8; ++j) {
+                    for (int j = 0; j < JB; ++j) {
                         const int ch = 4 * (2 * KH + s) + (lane >> 4);
                         b[j] = Xc[((jh + j) * 16 + brow) * 16 + (ch ^ brow)];
                     }
 #pragma unroll
                     for (int i = 0; i < TNB; ++i)
 #pragma unroll
-                        for (int j = 0; j < 8; ++j)
+                        for (int j = 0; j < JB; ++j)
                             acc[i][jh + j] = mfma16x16x32(ac[i][s], b[j], acc[i][jh + j]);
                 }
             }
