@@ -523,8 +523,9 @@ __device__ __forceinline__ void qgemm_tall_tile(h8 *Xs0, h8 *Xs1, const _Float16
     buf.zeros = make_rsrc(zeros, Np * (uint32_t)G * 2u);
 
     // Activation copies, global memory straight into LDS: copy i of a wavefront fills the 64 slots from
-    // 64*wave + 512*i, i.e. rows 4*wave + 32*i + lane/16; slot (row, pos) holds chunk pos ^ (row & 15).  Rows
-    // past M lie past the descriptor's size and read as zero; their results are never stored.
+    // 64*wave + 512*i, i.e. rows 4*wave + 32*i + lane/16; slot (row, pos) holds chunk pos ^ (row & 15).  The
+    // row is part of the lane offset, which the descriptor's range check covers (the scalar offset, which
+    // carries the group's bytes within the row, is not checked): rows past M read as zero and are never stored.
     const int xrow = 4 * wave + (lane >> 4), xch = (lane & 15) ^ (xrow & 15);
     const uint32_t xoff0 = ((uint32_t)(m0 + xrow) * (uint32_t)K + (uint32_t)xch * 8u) * 2u;
     const uint32_t xstep = 64u * (uint32_t)K; // 32 rows
@@ -538,7 +539,7 @@ __device__ __forceinline__ void qgemm_tall_tile(h8 *Xs0, h8 *Xs1, const _Float16
 
 #pragma unroll
     for (int i = 0; i < 8; ++i)
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(buf.x, &Xs0[64 * wave + 512 * i], 16, xoff0, xstep * i, 0, 0);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(buf.x, &Xs0[64 * wave + 512 * i], 16, xoff0 + xstep * i, 0, 0, 0);
 
     // integer zeros: one addition takes bias and zero away (see qgemm_tile)
     bool intz;
@@ -580,8 +581,8 @@ __device__ __forceinline__ void qgemm_tall_tile(h8 *Xs0, h8 *Xs1, const _Float16
                         WChunk<BITS> (&wl)[TNB]) {
 #pragma unroll
             for (int i = 0; i < 8; ++i)
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(buf.x, &Xn[64 * wave + 512 * i], 16, xoff0,
-                                                         (uint32_t)min(g + 1, G - 1) * 256u + xstep * i, 0, 0);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(buf.x, &Xn[64 * wave + 512 * i], 16, xoff0 + xstep * i,
+                                                         (uint32_t)min(g + 1, G - 1) * 256u, 0, 0);
             __builtin_amdgcn_sched_barrier(0); // the copies go out first: they have the whole iteration to land
             load_all(wl, g + 2);
             unpack_all(wn, an); // ahead of the MFMAs in program order: the scheduler fills their shadows with it
