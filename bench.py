@@ -52,7 +52,7 @@ SEED = 1
 # WRITE_SIZE, KiB per dispatch) scaled by what the same counters read for a 64 MiB device copy (FETCH_SIZE
 # reads 0.500 of the true bytes on this machine, WRITE_SIZE 1.000).  Valid only for the kernel sources whose
 # digest is recorded with it; bench.py reports null once they have changed.
-GEMM_TRAFFIC = {"kernel_digest": "6028a6ce06b7470a", "fetch_bytes": 820.2e6, "write_bytes": 174.1e6}  # profiles/qgemm_gemv_llama2-7b-block_hbm_traffic.txt
+GEMM_TRAFFIC = {"kernel_digest": "efcd1fc7f8bd8b14", "fetch_bytes": 820.1e6, "write_bytes": 174.1e6}  # profiles/qgemm_gemv_llama2-7b-block_hbm_traffic.txt
 
 
 SWAP_ENTRY = 4  # the matrix (gate) the transition leg swaps
