@@ -798,6 +798,34 @@ def test_qlinear_mixed_widths_within_a_matrix(fq, torch, M, case):
         col += w.N
 
 
+def test_qlinear_mixed_full_size_sampled(fq, torch):
+    """The benchmark's mixed matrix (4096 rows as 60/30/10 % at 2/3/4 bits, K = 4096) at M = 2048: the launch has
+    a 256-row tile for every compute unit, so the runs go through the 256-row tiles with a row pitch wider
+    than their own N (odd run widths included).  Sampled rows and columns against the oracle; guard bytes."""
+    K, M = 4096, 2048
+    runs = [(2433, 2), (1231, 3), (432, 4)]
+    rng = np.random.default_rng(17)
+    segs, sampled, cols_all, col0 = [], [], [], 0
+    for i, (N, bits) in enumerate(runs):
+        w, codes, s, z = make_matrix(fq, 900 + i, N, K, bits)
+        segs.append(w)
+        cols = np.unique(np.concatenate([rng.integers(0, N, size=64), [0, N - 1]]))
+        sampled.append(oracle.dequant(codes[cols], s[cols], z[cols]))
+        cols_all.append(col0 + cols)
+        col0 += N
+    X = fq_synth.activations(32, M, K)
+    out = Guarded(torch, M * col0 * 2)
+    fq.fq_qlinear_mixed(dev(torch, X), segs, out=out.half(M, col0))
+    torch.cuda.synchronize()
+    assert out.intact()
+    y = host16(out.half(M, col0))
+    assert np.all(np.isfinite(y.astype(np.float32)))
+    rows = np.unique(np.concatenate([rng.integers(0, M, size=48), [0, 255, 256, M - 1]]))
+    want = oracle.qlinear(X[rows], np.concatenate(sampled, axis=0))
+    got = y[np.ix_(rows, np.concatenate(cols_all))].astype(np.float64)
+    assert qerr(got, want) <= TOL
+
+
 def test_qlinear_mixed_rejects_bad_arguments(fq, torch):
     w, *_ = make_matrix(fq, 1, 64, 128, 4)
     x = dev(torch, fq_synth.activations(1, 2, 128))
