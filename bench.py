@@ -572,6 +572,40 @@ def main():
                 del cps, g1
         return table
 
+    def leg_same_process():
+        """The seven matrices of the block at M=2048 three ways in one process, repetitions interleaved (boxes
+        differ by several per cent among themselves, so only such figures compare): the 128-row tile kernels, the
+        256-row tile kernel, and the vendor's dense fp16 GEMM (torch.matmul on the dequantized matrix: the same
+        product with no unpacking)."""
+        reps_ab = 30
+        t128 = t256 = tvend = 0.0
+        for j, (N, K) in enumerate(shapes):
+            w = block[j][int(bitvec[j])]
+            xin = mm if K == FFN else u
+            o1 = torch.empty((M_FWD, N), dtype=torch.float16, device=dev)
+            o2 = torch.empty_like(o1)
+            wt = fq.fq_dequant(w, fp16=True).t()
+            fns = [lambda: fq.fq_qlinear(xin, w, out=o1, tile_rows=128), lambda: fq.fq_qlinear(xin, w, out=o1, tile_rows=256),
+                   lambda: torch.matmul(xin, wt, out=o2)]
+            for f in fns:
+                f()
+            torch.cuda.synchronize()
+            ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps_ab)]
+                  for _ in fns]
+            for r in range(reps_ab):
+                for i, f in enumerate(fns):
+                    ev[i][r][0].record()
+                    f()
+                    ev[i][r][1].record()
+            torch.cuda.synchronize()
+            m = [float(np.median([a.elapsed_time(b) for a, b in e])) for e in ev]
+            t128, t256, tvend = t128 + m[0], t256 + m[1], tvend + m[2]
+            del wt
+        return {"tflops_128_row_tiles": round(gemm_flops / t128 / 1e9, 1), "tflops_256_row_tiles": round(gemm_flops / t256 / 1e9, 1),
+                "tflops_vendor_dense_fp16": round(gemm_flops / tvend / 1e9, 1), "repetitions": reps_ab,
+                "note": "seven launches each, medians of interleaved repetitions; every third launch is the other kind, so each runs a little slower than alone"}
+
+    same_process = optional(leg_same_process)
     block_13b = optional(leg_13b)
     mixed_matrix = optional(leg_mixed_matrix)
     stream_read = optional(leg_stream_read)
@@ -626,6 +660,7 @@ def main():
             "ensemble_sweep_outside_the_step": full_stack,
             "transition_outside_the_step": transition,
             "gemv_large_outside_the_step": gemv_large,
+            "tile_heights_and_vendor_dense_same_process_outside_the_step": same_process,
             "gemv_m1": {"GBps_single_launches": round(block_bytes / gemv_ms_total / 1e6, 1),
                         "GBps_stack_decode": round(gemv_bytes / ms_dec / 1e6, 1),
                         "ms_stack_decode": round(ms_dec, 4), "ms_stack_decode_min": round(ms_dec_min, 4),
