@@ -223,13 +223,9 @@ __device__ __forceinline__ void gemv_body(const GemvJob job, int bj, const GemvI
 {
     constexpr int SUB = Fmt<BITS>::SUB, ROWS = Fmt<BITS>::ROWS, D = GemvDepth<BITS>::D, TILE = tile_dwords<BITS>();
     constexpr int NIN = GemvInputs<MODE>::N, STEP = 64 * GNW;
-    // vector loads one fill of the ring issues: planes, scales and zeros of every slot (none of them
-    // can merge: they are at least a kilobyte apart or come from different arrays)
     constexpr int F = SUB / S;
     constexpr bool WHOLE = F == 1;
     constexpr int NMETA = GemvSlot<BITS, S>::NMETA;
-    constexpr int RING_LOADS = D * ((WHOLE ? Fmt<BITS>::PLANES : (BITS == 2 ? 1 : BITS)) + NMETA);
-    static_assert(RING_LOADS < 64, "the wait below counts the ring's loads");
     const int G = K >> 7;
     const int T = (G + GNW - 1) / GNW; // groups per wavefront and supertile row
     const int GP = T * GNW;            // groups rounded up to whole turns of the wavefronts: the rest is zero
@@ -248,30 +244,23 @@ __device__ __forceinline__ void gemv_body(const GemvJob job, int bj, const GemvI
     const uint32_t *const packed = job.packed;
     const _Float16 *const scales = job.scales, *const zeros = job.zeros;
 
-    if (bj >= NU)
-        return; // uniform: nothing to do for this workgroup
+    if (bj >= NU) {
+        __builtin_amdgcn_s_waitcnt(FQ_WAIT_VMCNT0); // the kernel's copies into this workgroup's LDS land before it ends
+        return;                                     // uniform: nothing to do for this workgroup
+    }
     auto unit_row = [&](int ub) { return WHOLE ? ub : (ub / (8 * F)) * 8 + (ub & 7); };
     auto unit_part = [&](int ub) { return WHOLE ? 0 : (ub >> 3) & (F - 1); };
 
-    // ---- the input row first, copied from global memory straight into LDS (no registers): the
-    // staging below then waits for these copies only, not for the weights issued behind them.  The
-    // i-th copy of a wavefront fills 64 consecutive 16-byte slots, lane by lane; chunk indices past the
-    // end of the row are clamped (their slots are never read).
+    // ---- the input row is on its way already: the kernel issued its copies from global memory straight into
+    // `raw` (no registers) before it looked at its job; the staging below waits for these copies only, not
+    // for the weights issued behind them.
     const int chunks = K >> 3, trips = (chunks + STEP - 1) / STEP;
     const _Float16 *const src[3] = {in.a, in.b, in.c};
-    for (int t = 0; t < trips; ++t) {
-        const size_t off = (size_t)min(tid + STEP * t, chunks - 1) * 8;
-#pragma unroll
-        for (int i = 0; i < NIN; ++i)
-            __builtin_amdgcn_global_load_lds(src[i] + off, &raw[(i * trips + t) * STEP + 64 * wave], 16, 0, 0);
-    }
-    __builtin_amdgcn_sched_barrier(0); // the weights' loads stay behind the copies
-#ifndef FQ_GEMV_COUNTED_WAIT
-    // Plain order: the copies land before any weight load is issued.  Measured against the counted wait below
-    // (weights in flight while the copies land): the same on a 7B-shaped block, 0.8 % slower on a 13B-shaped one.
+    // The copies land before any weight load is issued.  Measured against the other order (weights issued behind
+    // the copies and left in flight by a counted wait): the same or slightly faster, and nothing here depends
+    // on how many loads the compiler places where.
     __builtin_amdgcn_s_waitcnt(FQ_WAIT_VMCNT0);
     lds_barrier();
-#endif
 
     // ---- weights: unconditional loads (indices clamped into the matrix) so that a wavefront only
     // ever waits for the oldest slot of its ring.
@@ -439,15 +428,6 @@ __device__ __forceinline__ void gemv_body(const GemvJob job, int bj, const GemvI
                 put(tid + STEP * t, v);
             }
     };
-    // Row 0 apart from the others: its copies were issued before the weights, so waiting for them leaves
-    // the weights in flight; later rows are fetched behind the weights and wait for everything.
-#ifdef FQ_GEMV_COUNTED_WAIT
-    // Counted wait (opt-in at build time): exactly the ring's RING_LOADS vector loads were issued behind the
-    // copies, so waiting until no more than that many are in flight means the copies have landed.  That count
-    // is a property of the compiled code: a build with this option checks it there and fails if it does not hold.
-    __builtin_amdgcn_s_waitcnt(gemv_wait_vmcnt(RING_LOADS)); // the copies of row 0 have landed ...
-    lds_barrier();                                           // ... in every wavefront
-#endif
     // Zero what no row writes: the groups past K (items on them then add nothing) and the sums of the
     // activation rows past M.
     for (int i = chunks * M + tid; i < GP * 16 * M; i += STEP)
@@ -594,6 +574,26 @@ __global__ __launch_bounds__(64 * GNW, 4) void gemv_stream_kernel(GemvInput in, 
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     __shared__ float part[2 * GNW];
+    // The input row first, before anything about the job is known (which matrix, which width: three dependent
+    // rounds of kernel-argument loads): row 0 of every input of the mode, copied from global memory straight into
+    // LDS.  The i-th copy of a wavefront fills 64 consecutive 16-byte slots, lane by lane; chunk indices past the
+    // end of the row are clamped (their slots are never read).  The destination is the region the bodies call
+    // `raw` (behind the staged activations and the three group arrays), the same for every width.
+    {
+        constexpr int NIN = GemvInputs<MODE>::N, STEP = 64 * GNW;
+        const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+        const int GP = (((K >> 7) + GNW - 1) / GNW) * GNW;
+        h8 *raw = reinterpret_cast<h8 *>(smem + (size_t)GP * 16 * M * 16 + 3 * (size_t)GP * 16 * 4);
+        const int chunks = K >> 3, trips = (chunks + STEP - 1) / STEP;
+        const _Float16 *const src[3] = {in.a, in.b, in.c};
+        for (int t = 0; t < trips; ++t) {
+            const size_t off = (size_t)min(tid + STEP * t, chunks - 1) * 8;
+#pragma unroll
+            for (int i = 0; i < NIN; ++i)
+                __builtin_amdgcn_global_load_lds(src[i] + off, &raw[(i * trips + t) * STEP + 64 * wave], 16, 0, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0); // nothing of the job selection moves ahead of the copies
+    }
     // the job of this workgroup, selected by value so that its fields stay in scalar registers
     GemvJob job = jobs.j[0];
     if (jobs.count > 1 && (int)blockIdx.x >= jobs.j[1].blk0)
