@@ -573,8 +573,8 @@ def main():
         return table
 
     def leg_same_process():
-        """The seven matrices of the block at M=2048 three ways in one process, repetitions interleaved (boxes
-        differ by several per cent among themselves, so only such figures compare): the 128-row tile kernels, the
+        """The seven matrices of the block at M=2048 three ways in one process, repetitions interleaved (GPUs of
+        the same model differ by several per cent among themselves, so only such figures compare): the 128-row tile kernels, the
         256-row tile kernel, and the vendor's dense fp16 GEMM (torch.matmul on the dequantized matrix: the same
         product with no unpacking)."""
         reps_ab = 30
