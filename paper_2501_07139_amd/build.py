@@ -32,9 +32,15 @@ def _hipcc() -> str:
     raise RuntimeError("hipcc not found")
 
 
+# The decode kernels take their inputs, M and K as the first ten dwords of their arguments; preloaded into scalar
+# registers, they let the kernel issue its first loads without a round trip to the argument buffer (older
+# firmware runs the compiler's fallback that loads them).
+PER_FILE_FLAGS = {"fq_gemv.hip": ["-mllvm", "-amdgpu-kernarg-preload-count=10"]}
+
+
 def _compile(src: str) -> str:
     obj = os.path.join(OBJ, os.path.splitext(src)[0] + ".o")
-    cmd = [_hipcc(), *FLAGS, "-x", "hip", "-c", os.path.join(CSRC, src), "-o", obj]
+    cmd = [_hipcc(), *FLAGS, *PER_FILE_FLAGS.get(src, []), "-x", "hip", "-c", os.path.join(CSRC, src), "-o", obj]
     res = subprocess.run(cmd, capture_output=True, text=True)
     noise = ("is not a recognized feature for this target", "argument unused during compilation")
     err = "\n".join(l for l in res.stderr.splitlines() if not any(n in l for n in noise))

@@ -568,10 +568,14 @@ __device__ __forceinline__ void gemv_body(const GemvJob job, int bj, const GemvI
     }
 }
 
-// Four wavefronts per SIMD, i.e. two workgroups per CU.
+// Four wavefronts per SIMD, i.e. two workgroups per CU.  The inputs, M and K come first and as plain pointers
+// and integers: the build asks the compiler to have these ten dwords preloaded into scalar registers at wavefront
+// start, so the copies of the input row go out without waiting for a load of the kernel arguments.
 template <int MODE, int MV>
-__global__ __launch_bounds__(64 * GNW, 4) void gemv_stream_kernel(GemvInput in, int M, int K, GemvJobs jobs)
+__global__ __launch_bounds__(64 * GNW, 4) void gemv_stream_kernel(const _Float16 *in_a, const _Float16 *in_b, const _Float16 *in_c,
+                                                                  _Float16 *in_aux, int M, int K, GemvJobs jobs)
 {
+    const GemvInput in = {in_a, in_b, in_c, in_aux, MODE};
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     __shared__ float part[2 * GNW];
     // The input row first, before anything about the job is known (which matrix, which width: three dependent
@@ -619,7 +623,7 @@ __global__ __launch_bounds__(64 * GNW, 4) void gemv_stream_kernel(GemvInput in, 
     }
 }
 
-typedef void (*GemvKernel)(GemvInput, int, int, GemvJobs);
+typedef void (*GemvKernel)(const _Float16 *, const _Float16 *, const _Float16 *, _Float16 *, int, int, GemvJobs);
 
 // One kernel per input mode, for a single activation row and for up to sixteen.
 GemvKernel gemv_kernel_for(int mode, int M, int *slot)
@@ -825,7 +829,7 @@ int fq_launch_gemv_multi(const fq_gemv_input &src, int M, const fq_packed_ref *w
         jobs.j[i] = GemvJob{nullptr, nullptr, nullptr, nullptr, 0, 0, blk0, 0, 0, 0};
     const GemvInput in = {static_cast<const _Float16 *>(src.a), static_cast<const _Float16 *>(src.b),
                           static_cast<const _Float16 *>(src.c), static_cast<_Float16 *>(src.aux), src.mode};
-    hipLaunchKernelGGL(kernel, dim3(blk0), dim3(64 * GNW), lds, st, in, M, w[0].K, jobs);
+    hipLaunchKernelGGL(kernel, dim3(blk0), dim3(64 * GNW), lds, st, in.a, in.b, in.c, in.aux, M, w[0].K, jobs);
     return (int)hipGetLastError();
 }
 
